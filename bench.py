@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the RanDeS hot path on one MI355X.
+
+One *step* is one pass of the whole hot path over one synthetic batch: merge
+(compress) the K task deltas once, then serve a stream of retrieve requests that
+cycle over the task ids.  The default workload is the Llama-7B-shaped bf16 stack
+(32 blocks, d = 4096, ffn 11008, K = 8, 64 requests).  Inputs are generated on
+the device and are resident in HBM before the timed region starts.
+
+Prints ONE JSON line: whole-step throughput in GB/s of algorithmic bytes
+(merge: K*b_in + b_merged per element; retrieve: b_merged + b_base + b_out per
+element), the HBM roofline of the dominant kernel (retrieve) and of the merge
+kernel, and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2505_11204_amd import binding as rb          # noqa: E402
+from paper_2505_11204_amd import workloads as wl        # noqa: E402
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+WORKLOADS = {
+    # name: (stack fn, storage dtype, K, requests, delta std, per-task scales?)
+    "llama_7b": (wl.llama_7b, "bf16", 8, 64, 5e-4, False),
+    "vit_l14": (wl.vit_l14, "f32", 20, 20, 1e-3, True),
+    "vit_b32": (wl.vit_b32, "f32", 8, 8, 1e-3, False),
+    "t5_base": (wl.t5_base, "bf16", 8, 8, 1e-3, False),
+    "tiny": (wl.tiny, "f32", 4, 4, 1e-3, False),
+}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="llama_7b", choices=sorted(WORKLOADS))
+    ap.add_argument("--requests", type=int, default=0, help="retrieve requests per step (0 = workload default)")
+    ap.add_argument("--merge-rows", type=int, default=0, help="rows per merge tile (0 = library default)")
+    ap.add_argument("--retrieve-rows", type=int, default=0, help="rows per retrieve tile (0 = library default)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-rows", type=int, default=1024)
+    return ap.parse_args()
+
+
+def cpu_baseline(stack, layers, deltas, base, seeds, dtype, n_requests, sample_rows):
+    """The oracle, as it stands, on the first `sample_rows` rows of every layer of
+    the first block (plus nothing else), with all host threads."""
+    import numpy as np  # noqa: F401
+    import oracle
+    code = {"f32": 0, "bf16": 1}[dtype]
+    # first block = the first occurrence of every group id; singletons are left out
+    seen, pick = set(), []
+    for idx, l in enumerate(stack):
+        if l.group >= 0 and l.group not in seen:
+            seen.add(l.group)
+            pick.append(idx)
+    sub = [(min(stack[i].rows, sample_rows), stack[i].cols, -1, stack[i].flags & wl.FLIP) for i in pick]
+    n_elem = sum(r * c for r, c, _, _ in sub)
+    K = len(seeds)
+    host_d = [[wl.to_numpy(deltas[i][p][:sub[q][0]]) for q, p in enumerate(pick)] for i in range(K)]
+    host_b = [wl.to_numpy(base[p][:sub[q][0]]) for q, p in enumerate(pick)]
+    threads = oracle.max_threads()
+    t0 = time.perf_counter()
+    merged = oracle.merge(sub, host_d, seeds, code, code, n_threads=threads)
+    t1 = time.perf_counter()
+    oracle.retrieve(sub, merged, host_b, seeds[0], 1.0, code, code, code, n_threads=threads)
+    t2 = time.perf_counter()
+    eb = 4 if dtype == "f32" else 2
+    bytes_merge = n_elem * (K * eb + eb)
+    bytes_retr = n_elem * 3 * eb
+    t_step = (t1 - t0) + n_requests * (t2 - t1)
+    return {
+        "value": (bytes_merge + n_requests * bytes_retr) / t_step / 1e9,
+        "unit": "GB/s",
+        "cores": threads,
+        "kind": "oracle",
+        "sample": "first %d rows of each of the %d matrices of block 0 (%d elements, K=%d): one merge %.3f s + "
+                  "one retrieve %.3f s, combined as 1 merge + %d retrieves" % (
+                      sample_rows, len(sub), n_elem, K, t1 - t0, t2 - t1, n_requests),
+        "merge_GBs": bytes_merge / (t1 - t0) / 1e9,
+        "retrieve_GBs": bytes_retr / (t2 - t1) / 1e9,
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path shards by rows with no communication; "
+              "see DESIGN.md); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    rb.lib()
+    torch.cuda.set_device(0)
+    stack_fn, dtype, K, n_req, delta_std, scaled = WORKLOADS[args.workload]
+    if args.requests:
+        n_req = args.requests
+    stack = stack_fn()
+    layers = [(l.rows, l.cols, l.group, l.flags) for l in stack]
+    n_elem = wl.n_elements(stack)
+    eb = 4 if dtype == "f32" else 2
+    seeds = [42 + i for i in range(K)]
+    scales = wl.task_scales(K, 1234) if scaled else None
+    rb.set_tile_rows(args.merge_rows, args.retrieve_rows)
+
+    base, deltas = wl.make_inputs(stack, K, dtype=dtype, device="cuda", data_seed=1234,
+                                  delta_std=delta_std, scales=scales)
+    td = wl.torch_dtype(dtype)
+    _, merged = wl.alloc_stack(stack, td, "cuda")
+    _, out = wl.alloc_stack(stack, td, "cuda")
+    lt = rb.LayerTable(layers)
+    t_deltas = rb.PtrTable([t for per in deltas for t in per], lt)
+    t_merged, t_base, t_out = rb.PtrTable(merged, lt), rb.PtrTable(base, lt), rb.PtrTable(out, lt)
+    torch.cuda.synchronize()
+
+    bytes_merge = n_elem * (K * eb + eb)
+    bytes_retr = n_elem * 3 * eb
+    bytes_step = bytes_merge + n_req * bytes_retr
+
+    def step(events=None):
+        if events is not None:
+            e0 = torch.cuda.Event(enable_timing=True); e0.record()
+        rb.merge(lt, t_deltas, seeds, merged=t_merged)
+        if events is not None:
+            e1 = torch.cuda.Event(enable_timing=True); e1.record()
+            events["merge"].append((e0, e1))
+        for q in range(n_req):
+            if events is not None:
+                a = torch.cuda.Event(enable_timing=True); a.record()
+            rb.retrieve(lt, t_merged, t_base, seeds[q % K], 1.0, out=t_out)
+            if events is not None:
+                b = torch.cuda.Event(enable_timing=True); b.record()
+                events["retrieve"].append((a, b))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = {"merge": [], "retrieve": []}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / max(args.steps, 1)
+
+    merge_ms = sorted(a.elapsed_time(b) for a, b in events["merge"])
+    retr_ms = sorted(a.elapsed_time(b) for a, b in events["retrieve"])
+    avg = lambda xs: sum(xs) / len(xs)          # noqa: E731
+    pct = lambda xs, p: xs[min(len(xs) - 1, int(p * len(xs)))]   # noqa: E731
+    retr_avg, merge_avg = avg(retr_ms), avg(merge_ms)
+    retr_gbs = bytes_retr / (retr_avg * 1e-3) / 1e9
+    merge_gbs = bytes_merge / (merge_avg * 1e-3) / 1e9
+
+    result = {
+        "metric": "merge & retrieve GB/s (bytes moved) and % of MI355X HBM peak",
+        "value": bytes_step / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": "%s-shaped stack: %d matrices, %d elements, %s storage with f32 arithmetic, K=%d, "
+                        "one merge + %d retrieve requests per step" % (args.workload, len(stack), n_elem, dtype, K, n_req),
+            "storage": dtype, "n_tasks": K, "requests_per_step": n_req, "lambda": 1.0,
+            "algorithmic_bytes_per_step": bytes_step,
+            "pct_of_hbm_peak": 100.0 * bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "merge": {"GBs": merge_gbs, "ms_avg": merge_avg, "ms_min": merge_ms[0], "bytes": bytes_merge,
+                      "pct_of_hbm_peak": 100.0 * merge_gbs / HBM_PEAK_GBS},
+            "retrieve": {"GBs": retr_gbs, "ms_avg": retr_avg, "ms_median": pct(retr_ms, 0.5),
+                         "ms_p95": pct(retr_ms, 0.95), "ms_min": retr_ms[0], "bytes": bytes_retr,
+                         "pct_of_hbm_peak": 100.0 * retr_gbs / HBM_PEAK_GBS},
+        },
+        "roofline": {"kernel": "retrieve_kernel", "bound": "hbm", "achieved": retr_gbs, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": retr_gbs / HBM_PEAK_GBS, "traffic": None},
+        "roofline_merge": {"kernel": "merge_kernel", "bound": "hbm", "achieved": merge_gbs, "peak": HBM_PEAK_GBS,
+                           "unit": "GB/s", "frac": merge_gbs / HBM_PEAK_GBS, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(stack, layers, deltas, base, seeds, dtype, n_req, args.cpu_sample_rows)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

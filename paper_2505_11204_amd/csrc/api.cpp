@@ -1,0 +1,504 @@
+// C ABI of the library (see include/randes.h): argument validation, plan cache,
+// table upload and kernel launches.  No arithmetic of the method happens on the
+// host except the layer permutations, which are pointer bookkeeping (Sec. 4.3).
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <list>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "launch.hpp"
+#include "plan.hpp"
+
+using namespace randes;
+
+namespace {
+
+thread_local std::string g_detail;   // text of the last failure on this thread
+
+int fail(int code, const std::string &why)
+{
+    g_detail = why;
+    return code;
+}
+
+int hip_fail(hipError_t e, const char *what)
+{
+    g_detail = std::string(what) + ": " + hipGetErrorString(e);
+    (void)hipGetLastError();   // clear the sticky error so the next call starts clean
+    return RANDES_EHIP;
+}
+
+bool dtype_ok(int d) { return d == RANDES_F32 || d == RANDES_BF16; }
+size_t elem_bytes(int d) { return d == RANDES_F32 ? 4 : 2; }
+bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+int g_merge_rows = 128, g_retrieve_rows = 128;
+
+// ------------------------------------------------------------------ plan cache
+struct CachedPlan {
+    std::string key;
+    int device = 0;
+    void *blob = nullptr;     // device tables
+    StreamArgs vec{}, scl{};
+};
+
+std::mutex g_mu;
+std::list<CachedPlan> g_plans;           // most recently used first
+constexpr size_t MAX_PLANS = 64;
+
+void append(std::string *k, const void *p, size_t n) { k->append((const char *)p, n); }
+
+CachedPlan *lookup(const std::string &key, int device)
+{
+    for (auto it = g_plans.begin(); it != g_plans.end(); ++it) {
+        if (it->device == device && it->key == key) {
+            g_plans.splice(g_plans.begin(), g_plans, it);
+            return &g_plans.front();
+        }
+    }
+    return nullptr;
+}
+
+// Lay the host plan out in one blob, upload it, and fill the kernel arguments.
+int upload(const HostPlan &hp, int n_tasks, CachedPlan *cp)
+{
+    auto pad = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    const SubPlan *sub[2] = { &hp.vec, &hp.scl };
+    size_t off_layers[2], off_srcs[2], off_tb[2], off = 0;
+    for (int s = 0; s < 2; ++s) {
+        off_layers[s] = off; off = pad(off + sub[s]->layers.size() * sizeof(LayerDev));
+        off_srcs[s] = off;   off = pad(off + sub[s]->srcs.size() * sizeof(void *));
+        off_tb[s] = off;     off = pad(off + sub[s]->tile_begin.size() * sizeof(uint32_t));
+    }
+    const size_t off_keys = off;
+    off = pad(off + hp.keys.size() * sizeof(uint32_t));
+    std::vector<char> host(off, 0);
+    for (int s = 0; s < 2; ++s) {
+        if (!sub[s]->layers.empty()) memcpy(host.data() + off_layers[s], sub[s]->layers.data(), sub[s]->layers.size() * sizeof(LayerDev));
+        if (!sub[s]->srcs.empty()) memcpy(host.data() + off_srcs[s], sub[s]->srcs.data(), sub[s]->srcs.size() * sizeof(void *));
+        if (!sub[s]->tile_begin.empty()) memcpy(host.data() + off_tb[s], sub[s]->tile_begin.data(), sub[s]->tile_begin.size() * sizeof(uint32_t));
+    }
+    if (!hp.keys.empty()) memcpy(host.data() + off_keys, hp.keys.data(), hp.keys.size() * sizeof(uint32_t));
+    hipError_t e = hipMalloc(&cp->blob, off);
+    if (e != hipSuccess) return hip_fail(e, "hipMalloc(plan tables)");
+    e = hipMemcpy(cp->blob, host.data(), off, hipMemcpyHostToDevice);
+    if (e != hipSuccess) { (void)hipFree(cp->blob); cp->blob = nullptr; return hip_fail(e, "hipMemcpy(plan tables)"); }
+    StreamArgs *args[2] = { &cp->vec, &cp->scl };
+    for (int s = 0; s < 2; ++s) {
+        StreamArgs &a = *args[s];
+        memset(&a, 0, sizeof(a));
+        const char *b = (const char *)cp->blob;
+        a.layers = (const LayerDev *)(b + off_layers[s]);
+        a.srcs = (const void *const *)(b + off_srcs[s]);
+        a.tile_begin = (const uint32_t *)(b + off_tb[s]);
+        a.keys = (const uint32_t *)(b + off_keys);
+        a.n_layers = (int32_t)sub[s]->layers.size();
+        a.n_tasks = n_tasks;
+        a.n_tiles = sub[s]->n_tiles;
+    }
+    return RANDES_OK;
+}
+
+// Add one slot layer to the vector or element-wise sub-plan.
+int place(HostPlan *hp, LayerDev d, const void *const *srcs, int n_srcs, bool vector_ok, int vec, int tile_rows)
+{
+    SubPlan &sp = vector_ok ? hp->vec : hp->scl;
+    const uint64_t tiles = plan_layer_geometry(&d, vector_ok ? vec : 1, tile_rows);
+    if (tiles == 0) return fail(RANDES_ENOTSUP, "layer too wide for 32-bit in-tile offsets");
+    if ((uint64_t)sp.n_tiles + tiles >= ((uint64_t)1 << 31)) return fail(RANDES_ENOTSUP, "too many tiles for one launch");
+    if (sp.tile_begin.empty()) sp.tile_begin.push_back(0);
+    sp.layers.push_back(d);
+    for (int i = 0; i < n_srcs; ++i) sp.srcs.push_back(srcs[i]);
+    sp.n_tiles += (uint32_t)tiles;
+    sp.tile_begin.push_back(sp.n_tiles);
+    return RANDES_OK;
+}
+
+struct Span { uintptr_t lo, hi; int tag; };
+
+// True if any span tagged 0 overlaps any span tagged 1.
+bool overlap(std::vector<Span> spans)
+{
+    std::sort(spans.begin(), spans.end(), [](const Span &a, const Span &b) { return a.lo < b.lo; });
+    uintptr_t hi0 = 0, hi1 = 0;   // furthest end seen so far per tag
+    for (const Span &s : spans) {
+        if (s.tag == 0) { if (s.lo < hi1) return true; hi0 = std::max(hi0, s.hi); }
+        else { if (s.lo < hi0) return true; hi1 = std::max(hi1, s.hi); }
+    }
+    return false;
+}
+
+int current_device(int *dev)
+{
+    hipError_t e = hipGetDevice(dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    return RANDES_OK;
+}
+
+CachedPlan *insert_plan(CachedPlan &&cp)
+{
+    g_plans.push_front(std::move(cp));
+    while (g_plans.size() > MAX_PLANS) {
+        if (g_plans.back().blob) (void)hipFree(g_plans.back().blob);
+        g_plans.pop_back();
+    }
+    return &g_plans.front();
+}
+
+}  // namespace
+
+extern "C" {
+
+int randes_layer_perm(uint64_t seed, int32_t group, int32_t group_size, int32_t *perm_out)
+{
+    if (!perm_out || group_size < 1) return fail(RANDES_EINVAL, "perm_out is NULL or group_size < 1");
+    layer_perm(seed, group, group_size, perm_out);
+    return RANDES_OK;
+}
+
+int randes_source_table(const randes_layer *layers, int32_t n_layers, uint64_t seed, int32_t *src_out)
+{
+    std::string why;
+    int rc = validate_layers(layers, n_layers, &why);
+    if (rc) return fail(rc, why);
+    if (!src_out) return fail(RANDES_EINVAL, "src_out is NULL");
+    std::vector<int32_t> src;
+    rc = build_source_table(layers, n_layers, seed, &src, &why);
+    if (rc) return fail(rc, why);
+    memcpy(src_out, src.data(), sizeof(int32_t) * (size_t)n_layers);
+    return RANDES_OK;
+}
+
+int randes_sign_mask(uint64_t seed, int32_t layer, int64_t cols, uint8_t *mask_out, void *hip_stream)
+{
+    if (!mask_out || cols < 1 || layer < 0) return fail(RANDES_EINVAL, "mask_out is NULL, cols < 1 or layer < 0");
+    if (cols >= (int64_t)1 << 31) return fail(RANDES_ENOTSUP, "cols >= 2^31");
+    hipError_t e = launch_sign_mask((uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32), (uint32_t)layer, cols,
+                                    mask_out, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail(e, "sign_mask launch");
+    return RANDES_OK;
+}
+
+int randes_merge(const randes_layer *layers, int32_t n_layers,
+                 const void *const *deltas, int32_t n_tasks, const uint64_t *seeds,
+                 randes_dtype delta_dtype, void *const *merged, randes_dtype merged_dtype, void *hip_stream)
+{
+    std::string why;
+    int rc = validate_layers(layers, n_layers, &why);
+    if (rc) return fail(rc, why);
+    if (!deltas || !seeds || !merged) return fail(RANDES_EINVAL, "deltas, seeds or merged is NULL");
+    if (n_tasks < 1) return fail(RANDES_EINVAL, "n_tasks < 1");
+    if (n_tasks > RANDES_MAX_TASKS) return fail(RANDES_ENOTSUP, "n_tasks above RANDES_MAX_TASKS");
+    if (!dtype_ok(delta_dtype) || !dtype_ok(merged_dtype)) return fail(RANDES_EINVAL, "unknown dtype");
+    for (int64_t q = 0; q < (int64_t)n_tasks * n_layers; ++q)
+        if (!deltas[q]) return fail(RANDES_EINVAL, "NULL delta pointer");
+    for (int32_t l = 0; l < n_layers; ++l)
+        if (!merged[l]) return fail(RANDES_EINVAL, "NULL merged pointer");
+
+    int dev;
+    if ((rc = current_device(&dev))) return rc;
+    const int32_t tile_rows = g_merge_rows;
+    std::string key;
+    const int32_t head[6] = { PLAN_MERGE, n_layers, n_tasks, (int32_t)delta_dtype, (int32_t)merged_dtype, tile_rows };
+    append(&key, head, sizeof(head));
+    append(&key, layers, sizeof(randes_layer) * (size_t)n_layers);
+    append(&key, deltas, sizeof(void *) * (size_t)n_tasks * (size_t)n_layers);
+    append(&key, seeds, sizeof(uint64_t) * (size_t)n_tasks);
+    append(&key, merged, sizeof(void *) * (size_t)n_layers);
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    CachedPlan *cp = lookup(key, dev);
+    if (!cp) {
+        // the superposition must not overwrite its own inputs
+        std::vector<Span> spans;
+        for (int32_t l = 0; l < n_layers; ++l) {
+            const size_t n = (size_t)layers[l].rows * (size_t)layers[l].cols;
+            spans.push_back({ (uintptr_t)merged[l], (uintptr_t)merged[l] + n * elem_bytes(merged_dtype), 0 });
+            for (int32_t i = 0; i < n_tasks; ++i) {
+                const void *p = deltas[(size_t)i * n_layers + l];
+                spans.push_back({ (uintptr_t)p, (uintptr_t)p + n * elem_bytes(delta_dtype), 1 });
+            }
+        }
+        if (overlap(spans)) return fail(RANDES_EINVAL, "merged overlaps a delta");
+
+        HostPlan hp;
+        std::vector<std::vector<int32_t>> src((size_t)n_tasks);
+        for (int32_t i = 0; i < n_tasks; ++i) {
+            rc = build_source_table(layers, n_layers, seeds[i], &src[(size_t)i], &why);
+            if (rc) return fail(rc, why);
+            hp.keys.push_back((uint32_t)(seeds[i] & 0xffffffffu));
+            hp.keys.push_back((uint32_t)(seeds[i] >> 32));
+        }
+        const int vec = merge_vec(delta_dtype);
+        std::vector<const void *> ptrs((size_t)n_tasks);
+        for (int32_t l = 0; l < n_layers; ++l) {
+            LayerDev d{};
+            d.dst = merged[l];
+            d.rows = (int32_t)layers[l].rows;
+            d.cols = (int32_t)layers[l].cols;
+            d.layer_id = (uint32_t)l;
+            d.flip = (layers[l].flags & RANDES_FLIP) ? 1u : 0u;
+            bool vector_ok = (layers[l].cols % vec) == 0 && aligned16(merged[l]);
+            for (int32_t i = 0; i < n_tasks; ++i) {
+                ptrs[(size_t)i] = deltas[(size_t)i * n_layers + src[(size_t)i][(size_t)l]];
+                vector_ok = vector_ok && aligned16(ptrs[(size_t)i]);
+            }
+            if ((rc = place(&hp, d, ptrs.data(), n_tasks, vector_ok, vec, tile_rows))) return rc;
+        }
+        CachedPlan fresh;
+        fresh.key = key;
+        fresh.device = dev;
+        if ((rc = upload(hp, n_tasks, &fresh))) return rc;
+        cp = insert_plan(std::move(fresh));
+    }
+    hipStream_t s = (hipStream_t)hip_stream;
+    hipError_t e = launch_merge(cp->vec, 1, delta_dtype, merged_dtype, s);
+    if (e != hipSuccess) return hip_fail(e, "merge launch");
+    e = launch_merge(cp->scl, 0, delta_dtype, merged_dtype, s);
+    if (e != hipSuccess) return hip_fail(e, "merge launch (element-wise)");
+    return RANDES_OK;
+}
+
+int randes_retrieve(const randes_layer *layers, int32_t n_layers,
+                    const void *const *merged, randes_dtype merged_dtype,
+                    const void *const *base, randes_dtype base_dtype,
+                    uint64_t seed, float lambda,
+                    void *const *out, randes_dtype out_dtype, void *hip_stream)
+{
+    std::string why;
+    int rc = validate_layers(layers, n_layers, &why);
+    if (rc) return fail(rc, why);
+    if (!merged || !base || !out) return fail(RANDES_EINVAL, "merged, base or out is NULL");
+    if (!dtype_ok(merged_dtype) || !dtype_ok(base_dtype) || !dtype_ok(out_dtype)) return fail(RANDES_EINVAL, "unknown dtype");
+    if (!std::isfinite(lambda)) return fail(RANDES_EINVAL, "lambda is not finite");
+    for (int32_t l = 0; l < n_layers; ++l)
+        if (!merged[l] || !base[l] || !out[l]) return fail(RANDES_EINVAL, "NULL layer pointer");
+
+    int dev;
+    if ((rc = current_device(&dev))) return rc;
+    const int32_t tile_rows = g_retrieve_rows;
+    std::string key;
+    const int32_t head[6] = { PLAN_RETRIEVE, n_layers, (int32_t)merged_dtype, (int32_t)base_dtype, (int32_t)out_dtype, tile_rows };
+    append(&key, head, sizeof(head));
+    append(&key, layers, sizeof(randes_layer) * (size_t)n_layers);
+    append(&key, merged, sizeof(void *) * (size_t)n_layers);
+    append(&key, base, sizeof(void *) * (size_t)n_layers);
+    append(&key, out, sizeof(void *) * (size_t)n_layers);
+    append(&key, &seed, sizeof(seed));
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    CachedPlan *cp = lookup(key, dev);
+    if (!cp) {
+        std::vector<Span> a, b;
+        for (int32_t l = 0; l < n_layers; ++l) {
+            const size_t n = (size_t)layers[l].rows * (size_t)layers[l].cols;
+            a.push_back({ (uintptr_t)out[l], (uintptr_t)out[l] + n * elem_bytes(out_dtype), 0 });
+            a.push_back({ (uintptr_t)merged[l], (uintptr_t)merged[l] + n * elem_bytes(merged_dtype), 1 });
+            if (out[l] != base[l] || out_dtype != base_dtype) {
+                b.push_back({ (uintptr_t)out[l], (uintptr_t)out[l] + n * elem_bytes(out_dtype), 0 });
+                b.push_back({ (uintptr_t)base[l], (uintptr_t)base[l] + n * elem_bytes(base_dtype), 1 });
+            }
+        }
+        if (overlap(a)) return fail(RANDES_EINVAL, "out overlaps merged");
+        if (overlap(b)) return fail(RANDES_EINVAL, "out partially overlaps base");
+
+        HostPlan hp;
+        std::vector<int32_t> src;
+        rc = build_source_table(layers, n_layers, seed, &src, &why);
+        if (rc) return fail(rc, why);
+        const int vec = retrieve_vec(merged_dtype, base_dtype);
+        for (int32_t l = 0; l < n_layers; ++l) {
+            const int32_t t = src[(size_t)l];
+            LayerDev d{};
+            d.dst = out[t];
+            d.a = merged[l];
+            d.b = base[t];
+            d.rows = (int32_t)layers[l].rows;
+            d.cols = (int32_t)layers[l].cols;
+            d.layer_id = (uint32_t)l;
+            d.flip = (layers[l].flags & RANDES_FLIP) ? 1u : 0u;
+            const bool vector_ok = (layers[l].cols % vec) == 0 && aligned16(d.dst) && aligned16(d.a) && aligned16(d.b);
+            if ((rc = place(&hp, d, nullptr, 0, vector_ok, vec, tile_rows))) return rc;
+        }
+        CachedPlan fresh;
+        fresh.key = key;
+        fresh.device = dev;
+        if ((rc = upload(hp, 1, &fresh))) return rc;
+        cp = insert_plan(std::move(fresh));
+    }
+    StreamArgs av = cp->vec, as = cp->scl;
+    av.key_lo = as.key_lo = (uint32_t)(seed & 0xffffffffu);
+    av.key_hi = as.key_hi = (uint32_t)(seed >> 32);
+    av.lambda = as.lambda = lambda;
+    hipStream_t s = (hipStream_t)hip_stream;
+    hipError_t e = launch_retrieve(av, 1, merged_dtype, base_dtype, out_dtype, s);
+    if (e != hipSuccess) return hip_fail(e, "retrieve launch");
+    e = launch_retrieve(as, 0, merged_dtype, base_dtype, out_dtype, s);
+    if (e != hipSuccess) return hip_fail(e, "retrieve launch (element-wise)");
+    return RANDES_OK;
+}
+
+int randes_update(const randes_layer *layers, int32_t n_layers,
+                  void *const *merged, randes_dtype merged_dtype,
+                  const void *const *delta, randes_dtype delta_dtype,
+                  uint64_t seed, int32_t remove, void *hip_stream)
+{
+    std::string why;
+    int rc = validate_layers(layers, n_layers, &why);
+    if (rc) return fail(rc, why);
+    if (!merged || !delta) return fail(RANDES_EINVAL, "merged or delta is NULL");
+    if (!dtype_ok(merged_dtype) || !dtype_ok(delta_dtype)) return fail(RANDES_EINVAL, "unknown dtype");
+    for (int32_t l = 0; l < n_layers; ++l)
+        if (!merged[l] || !delta[l]) return fail(RANDES_EINVAL, "NULL layer pointer");
+
+    int dev;
+    if ((rc = current_device(&dev))) return rc;
+    const int32_t tile_rows = g_retrieve_rows;
+    std::string key;
+    const int32_t head[5] = { PLAN_UPDATE, n_layers, (int32_t)merged_dtype, (int32_t)delta_dtype, tile_rows };
+    append(&key, head, sizeof(head));
+    append(&key, layers, sizeof(randes_layer) * (size_t)n_layers);
+    append(&key, merged, sizeof(void *) * (size_t)n_layers);
+    append(&key, delta, sizeof(void *) * (size_t)n_layers);
+    append(&key, &seed, sizeof(seed));
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    CachedPlan *cp = lookup(key, dev);
+    if (!cp) {
+        std::vector<Span> spans;
+        for (int32_t l = 0; l < n_layers; ++l) {
+            const size_t n = (size_t)layers[l].rows * (size_t)layers[l].cols;
+            spans.push_back({ (uintptr_t)merged[l], (uintptr_t)merged[l] + n * elem_bytes(merged_dtype), 0 });
+            spans.push_back({ (uintptr_t)delta[l], (uintptr_t)delta[l] + n * elem_bytes(delta_dtype), 1 });
+        }
+        if (overlap(spans)) return fail(RANDES_EINVAL, "merged overlaps delta");
+        HostPlan hp;
+        std::vector<int32_t> src;
+        rc = build_source_table(layers, n_layers, seed, &src, &why);
+        if (rc) return fail(rc, why);
+        const int vec = update_vec(merged_dtype, delta_dtype);
+        for (int32_t l = 0; l < n_layers; ++l) {
+            LayerDev d{};
+            d.dst = merged[l];
+            d.a = delta[src[(size_t)l]];
+            d.rows = (int32_t)layers[l].rows;
+            d.cols = (int32_t)layers[l].cols;
+            d.layer_id = (uint32_t)l;
+            d.flip = (layers[l].flags & RANDES_FLIP) ? 1u : 0u;
+            const bool vector_ok = (layers[l].cols % vec) == 0 && aligned16(d.dst) && aligned16(d.a);
+            if ((rc = place(&hp, d, nullptr, 0, vector_ok, vec, tile_rows))) return rc;
+        }
+        CachedPlan fresh;
+        fresh.key = key;
+        fresh.device = dev;
+        if ((rc = upload(hp, 1, &fresh))) return rc;
+        cp = insert_plan(std::move(fresh));
+    }
+    StreamArgs av = cp->vec, as = cp->scl;
+    av.key_lo = as.key_lo = (uint32_t)(seed & 0xffffffffu);
+    av.key_hi = as.key_hi = (uint32_t)(seed >> 32);
+    av.negate = as.negate = remove ? 1u : 0u;
+    hipStream_t s = (hipStream_t)hip_stream;
+    hipError_t e = launch_update(av, 1, merged_dtype, delta_dtype, s);
+    if (e != hipSuccess) return hip_fail(e, "update launch");
+    e = launch_update(as, 0, merged_dtype, delta_dtype, s);
+    if (e != hipSuccess) return hip_fail(e, "update launch (element-wise)");
+    return RANDES_OK;
+}
+
+int randes_lora_materialize_batched(int32_t n, const void *const *Bs, const void *const *As,
+                                    const int64_t *rows, const int64_t *cols, int32_t rank,
+                                    float scale, randes_dtype ab_dtype,
+                                    void *const *outs, randes_dtype out_dtype, void *hip_stream)
+{
+    if (n < 1 || !Bs || !As || !rows || !cols || !outs) return fail(RANDES_EINVAL, "NULL array or n < 1");
+    if (rank < 1) return fail(RANDES_EINVAL, "rank < 1");
+    if (!dtype_ok(ab_dtype) || !dtype_ok(out_dtype)) return fail(RANDES_EINVAL, "unknown dtype");
+    if (!std::isfinite(scale)) return fail(RANDES_EINVAL, "scale is not finite");
+    std::vector<LoraItem> items((size_t)n);
+    uint64_t tiles = 0;
+    for (int32_t q = 0; q < n; ++q) {
+        if (!Bs[q] || !As[q] || !outs[q]) return fail(RANDES_EINVAL, "NULL matrix pointer");
+        if (rows[q] < 1 || cols[q] < 1) return fail(RANDES_EINVAL, "rows < 1 or cols < 1");
+        if (rows[q] >= (int64_t)1 << 31 || cols[q] >= (int64_t)1 << 31) return fail(RANDES_ENOTSUP, "rows or cols >= 2^31");
+        LoraItem &it = items[(size_t)q];
+        it.B = Bs[q]; it.A = As[q]; it.out = outs[q];
+        it.rows = (int32_t)rows[q]; it.cols = (int32_t)cols[q];
+        it.tiles_x = (uint32_t)((cols[q] + LORA_TILE_N - 1) / LORA_TILE_N);
+        it.tile_begin = (uint32_t)tiles;
+        tiles += (uint64_t)it.tiles_x * (uint64_t)((rows[q] + LORA_TILE_M - 1) / LORA_TILE_M);
+        if (tiles >= ((uint64_t)1 << 31)) return fail(RANDES_ENOTSUP, "too many tiles for one launch");
+    }
+    int dev, rc;
+    if ((rc = current_device(&dev))) return rc;
+    std::string key;
+    const int32_t head[2] = { 100, n };
+    append(&key, head, sizeof(head));
+    append(&key, items.data(), sizeof(LoraItem) * items.size());
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    CachedPlan *cp = lookup(key, dev);
+    if (!cp) {
+        CachedPlan fresh;
+        fresh.key = key;
+        fresh.device = dev;
+        hipError_t e = hipMalloc(&fresh.blob, sizeof(LoraItem) * items.size());
+        if (e != hipSuccess) return hip_fail(e, "hipMalloc(lora table)");
+        e = hipMemcpy(fresh.blob, items.data(), sizeof(LoraItem) * items.size(), hipMemcpyHostToDevice);
+        if (e != hipSuccess) { (void)hipFree(fresh.blob); return hip_fail(e, "hipMemcpy(lora table)"); }
+        cp = insert_plan(std::move(fresh));
+    }
+    hipError_t e = launch_lora((const LoraItem *)cp->blob, n, (uint32_t)tiles, rank, scale, ab_dtype, out_dtype,
+                               (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail(e, "lora launch");
+    return RANDES_OK;
+}
+
+int randes_lora_materialize(const void *B, const void *A, int64_t rows, int64_t cols, int32_t rank,
+                            float scale, randes_dtype ab_dtype,
+                            void *delta_out, randes_dtype out_dtype, void *hip_stream)
+{
+    return randes_lora_materialize_batched(1, &B, &A, &rows, &cols, rank, scale, ab_dtype, &delta_out, out_dtype, hip_stream);
+}
+
+const char *randes_strerror(int code)
+{
+    switch (code) {
+    case RANDES_OK: return "ok";
+    case RANDES_EINVAL: return g_detail.empty() ? "invalid argument" : g_detail.c_str();
+    case RANDES_ENOTSUP: return g_detail.empty() ? "not supported" : g_detail.c_str();
+    case RANDES_EHIP: return g_detail.empty() ? "HIP runtime failure" : g_detail.c_str();
+    default: return "unknown error code";
+    }
+}
+
+int randes_shutdown(void)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    int rc = RANDES_OK;
+    for (CachedPlan &cp : g_plans) {
+        if (cp.blob) {
+            hipError_t e = hipFree(cp.blob);
+            if (e != hipSuccess) rc = hip_fail(e, "hipFree(plan tables)");
+        }
+    }
+    g_plans.clear();
+    return rc;
+}
+
+int randes_set_tile_rows(int32_t merge_rows, int32_t retrieve_rows)
+{
+    if (merge_rows < 0 || retrieve_rows < 0 || merge_rows > (1 << 20) || retrieve_rows > (1 << 20))
+        return fail(RANDES_EINVAL, "tile rows out of range");
+    std::lock_guard<std::mutex> lock(g_mu);
+    g_merge_rows = merge_rows ? merge_rows : 128;
+    g_retrieve_rows = retrieve_rows ? retrieve_rows : 128;
+    return RANDES_OK;
+}
+
+}  // extern "C"

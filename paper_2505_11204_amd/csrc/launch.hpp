@@ -1,0 +1,40 @@
+// Launchers of the gfx950 kernels, callable from plain C++ host code.
+#pragma once
+#include <hip/hip_runtime_api.h>
+#include <stdint.h>
+
+#include "plan.hpp"
+
+namespace randes {
+
+constexpr int DT_F32 = 0, DT_BF16 = 1;
+
+// vec = 0 launches the element-wise variant (one column per lane).
+hipError_t launch_merge(const StreamArgs &a, int vec, int dt_in, int dt_out, hipStream_t s);
+hipError_t launch_retrieve(const StreamArgs &a, int vec, int dt_merged, int dt_base, int dt_out, hipStream_t s);
+hipError_t launch_update(const StreamArgs &a, int vec, int dt_merged, int dt_delta, hipStream_t s);
+hipError_t launch_sign_mask(uint32_t key_lo, uint32_t key_hi, uint32_t layer, int64_t cols,
+                            uint8_t *mask_out, hipStream_t s);
+
+// One matrix of a LoRA batch.
+struct LoraItem {
+    const void *B;   // rows x rank
+    const void *A;   // rank x cols
+    void *out;       // rows x cols
+    int32_t rows, cols;
+    uint32_t tiles_x;     // workgroup tiles along the columns
+    uint32_t tile_begin;  // first workgroup of this matrix
+};
+hipError_t launch_lora(const LoraItem *items_dev, int32_t n_items, uint32_t n_tiles, int32_t rank, float scale,
+                       int dt_ab, int dt_out, hipStream_t s);
+
+// Columns per lane of the vector kernels for a call whose widest-count stream
+// holds bf16 (8) or only f32 (4).
+int merge_vec(int dt_in);
+int retrieve_vec(int dt_merged, int dt_base);
+int update_vec(int dt_merged, int dt_delta);
+
+// Workgroup tile of the LoRA kernel.
+constexpr int LORA_TILE_M = 32, LORA_TILE_N = 128;
+
+}  // namespace randes

@@ -1,0 +1,102 @@
+// Host-side planning: argument checks, layer permutations and source tables,
+// tile geometry.  Pure C++: nothing here needs a GPU.
+#include "plan.hpp"
+
+#include <algorithm>
+#include <map>
+#include <numeric>
+
+#include "philox.hpp"
+
+namespace randes {
+
+// sigma ~ S_G (Sec. 4.3): every position draws a 64-bit key from the generator;
+// sigma is the stable ascending argsort of the keys.
+void layer_perm(uint64_t seed, int32_t group, int32_t group_size, int32_t *perm_out)
+{
+    const uint32_t klo = (uint32_t)(seed & 0xffffffffu), khi = (uint32_t)(seed >> 32);
+    std::vector<uint64_t> keys((size_t)group_size);
+    for (int32_t k = 0; k < group_size; ++k) {
+        const u32x4_t o = philox4x32_10((uint32_t)k, (uint32_t)group, STREAM_PERM, 0u, klo, khi);
+        keys[(size_t)k] = ((uint64_t)o.w[0] << 32) | (uint64_t)o.w[1];
+    }
+    std::iota(perm_out, perm_out + group_size, 0);
+    std::stable_sort(perm_out, perm_out + group_size,
+                     [&](int32_t a, int32_t b) { return keys[(size_t)a] < keys[(size_t)b]; });
+}
+
+int validate_layers(const randes_layer *layers, int32_t n_layers, std::string *why)
+{
+    if (!layers || n_layers < 1) { *why = "layers is NULL or n_layers < 1"; return RANDES_EINVAL; }
+    for (int32_t l = 0; l < n_layers; ++l) {
+        if (layers[l].rows < 1 || layers[l].cols < 1) { *why = "layer with rows < 1 or cols < 1"; return RANDES_EINVAL; }
+        if (layers[l].cols >= (int64_t)1 << 31 || layers[l].rows >= (int64_t)1 << 31) {
+            *why = "layer with rows or cols >= 2^31"; return RANDES_ENOTSUP;
+        }
+        if (layers[l].flags & ~(RANDES_FLIP | RANDES_SHUFFLE | RANDES_SHIFT)) { *why = "unknown layer flag"; return RANDES_EINVAL; }
+    }
+    return RANDES_OK;
+}
+
+static bool movable(const randes_layer &l) { return l.group >= 0 && (l.flags & (RANDES_SHUFFLE | RANDES_SHIFT)); }
+
+int build_source_table(const randes_layer *layers, int32_t n_layers, uint64_t seed,
+                       std::vector<int32_t> *src, std::string *why)
+{
+    src->resize((size_t)n_layers);
+    std::iota(src->begin(), src->end(), 0);
+    std::map<int32_t, std::vector<int32_t>> groups;   // group id -> member layers, ascending
+    for (int32_t l = 0; l < n_layers; ++l)
+        if (movable(layers[l])) groups[layers[l].group].push_back(l);
+    std::vector<int32_t> perm;
+    for (const auto &kv : groups) {
+        const std::vector<int32_t> &mem = kv.second;
+        const int32_t G = (int32_t)mem.size();
+        bool shift = false;
+        for (int32_t l : mem) {
+            if (layers[l].rows != layers[mem[0]].rows || layers[l].cols != layers[mem[0]].cols) {
+                *why = "layers of one shuffle group differ in shape"; return RANDES_EINVAL;
+            }
+            shift = shift || (layers[l].flags & RANDES_SHIFT);
+        }
+        perm.resize((size_t)G);
+        if (shift) {
+            // one position deeper with wrap-around: slot k+1 receives layer k
+            for (int32_t k = 0; k < G; ++k) perm[(size_t)k] = (k + G - 1) % G;
+        } else {
+            layer_perm(seed, kv.first, G, perm.data());
+        }
+        for (int32_t k = 0; k < G; ++k) (*src)[(size_t)mem[(size_t)k]] = mem[(size_t)perm[(size_t)k]];
+    }
+    return RANDES_OK;
+}
+
+uint64_t plan_layer_geometry(LayerDev *d, int vec, int tile_rows)
+{
+    const uint64_t cols = (uint64_t)d->cols, rows = (uint64_t)d->rows;
+    // waves along the columns: the widest arrangement that wastes the fewest lanes
+    uint32_t best_shift = 0;
+    uint64_t best_waste = ~0ull;
+    for (int sh = 2; sh >= 0; --sh) {
+        const uint64_t cw = (uint64_t)(64 * vec) << sh;
+        const uint64_t waste = (cols + cw - 1) / cw * cw - cols;
+        if (waste < best_waste) { best_waste = waste; best_shift = (uint32_t)sh; }
+    }
+    d->wx_shift = best_shift;
+    d->wx = 1u << best_shift;
+    const uint64_t cw = (uint64_t)(64 * vec) << best_shift;
+    d->n_cb = (uint32_t)((cols + cw - 1) / cw);
+    // in-tile byte offsets are 32-bit: (tile_rows + rows in flight) * cols * 4 must stay below 2^31
+    const uint64_t row_bytes = cols * 4;
+    const uint64_t max_rows = ((uint64_t)1 << 31) / row_bytes;
+    if (max_rows < 17) return 0;
+    uint64_t tr = (uint64_t)tile_rows;
+    if (tr > max_rows - 16) tr = max_rows - 16;
+    if (tr > rows) tr = rows;
+    if (tr < 1) tr = 1;
+    d->tile_rows = (uint32_t)tr;
+    const uint64_t n_rc = (rows + tr - 1) / tr;
+    return n_rc * d->n_cb;
+}
+
+}  // namespace randes

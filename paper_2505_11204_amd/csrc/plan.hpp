@@ -1,0 +1,72 @@
+// Host-side plan of one merge / retrieve / update call and the device-resident
+// tables the streaming kernels read.  A plan turns the caller's layer list and
+// pointer arrays into: the per-model source tables (Sec. 4.3: the shuffle is a
+// pointer reallocation), per-layer descriptors, and a tile decomposition.
+#pragma once
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/randes.h"
+
+namespace randes {
+
+// One slot layer as a kernel sees it.  Pointers are device pointers.
+struct LayerDev {
+    void *dst;          // merge/update: merged[l];  retrieve: out[src(l)]
+    const void *a;      // retrieve: merged[l];      update: delta[src(l)]
+    const void *b;      // retrieve: base[src(l)]
+    int32_t rows;
+    int32_t cols;
+    uint32_t layer_id;  // slot index l: the generator's layer coordinate
+    uint32_t flip;      // 1 if the layer takes the sign flip
+    uint32_t n_cb;      // column blocks per row chunk
+    uint32_t tile_rows; // rows per tile
+    uint32_t wx;        // waves of a workgroup laid along the columns (1, 2 or 4)
+    uint32_t wx_shift;  // log2(wx)
+};
+
+// What a streaming kernel receives by value.
+struct StreamArgs {
+    const LayerDev *layers;       // n_layers
+    const void *const *srcs;      // merge only: [n_layers][n_tasks] source pointers
+    const uint32_t *tile_begin;   // n_layers + 1 prefix sums of tiles
+    const uint32_t *keys;         // merge only: [n_tasks][2] = (seed low, seed high)
+    int32_t n_layers;
+    int32_t n_tasks;
+    uint32_t n_tiles;
+    uint32_t key_lo, key_hi;      // retrieve / update: the one model's seed
+    float lambda;                 // retrieve
+    uint32_t negate;              // update: 1 removes the model
+};
+
+// A sub-plan: the layers one kernel variant handles (vector or element-wise).
+struct SubPlan {
+    std::vector<LayerDev> layers;
+    std::vector<const void *> srcs;     // merge
+    std::vector<uint32_t> tile_begin;
+    uint32_t n_tiles = 0;
+};
+
+struct HostPlan {
+    SubPlan vec, scl;
+    std::vector<uint32_t> keys;
+};
+
+enum PlanKind { PLAN_MERGE = 1, PLAN_RETRIEVE = 2, PLAN_UPDATE = 3 };
+
+int validate_layers(const randes_layer *layers, int32_t n_layers, std::string *why);
+
+// src[l] = layer of this model that lands in slot l.
+int build_source_table(const randes_layer *layers, int32_t n_layers, uint64_t seed,
+                       std::vector<int32_t> *src, std::string *why);
+
+void layer_perm(uint64_t seed, int32_t group, int32_t group_size, int32_t *perm_out);
+
+// Fill the geometry (n_cb, wx, tile_rows) of one descriptor for lanes that own
+// `vec` columns each; returns the layer's tile count, or 0 if the layer is too
+// wide for 32-bit in-tile offsets.
+uint64_t plan_layer_geometry(LayerDev *d, int vec, int tile_rows);
+
+}  // namespace randes

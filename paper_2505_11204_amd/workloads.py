@@ -183,11 +183,12 @@ def from_numpy(a, dtype):
 
 def shadow_rows(rows, n_pick, seed):
     """Row indices to sample from a layer for full-size parity: the first and
-    last rows, rows around multiples of 32 and 64 (tile edges), and a few
-    seeded random ones; sorted and unique, at most ``rows``."""
+    last rows, rows around multiples of 128 (tile edges), and a few seeded random
+    ones; sorted and unique.  Depends on ``rows`` and ``seed`` only, so layers
+    that can trade places in a shuffle sample the same rows."""
     g = torch.Generator(device="cpu")
-    g.manual_seed(seed)
-    fixed = [0, 1, 31, 32, 33, 63, 64, 65, rows // 2, rows - 2, rows - 1]
+    g.manual_seed(seed + rows)
+    fixed = [0, 1, 2, 3, 127, 128, 129, rows // 2, rows - 129, rows - 128, rows - 2, rows - 1]
     rnd = torch.randint(0, rows, (max(n_pick - len(fixed), 0),), generator=g).tolist()
     picks = sorted({r for r in fixed + rnd if 0 <= r < rows})
     return picks

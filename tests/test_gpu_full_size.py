@@ -1,0 +1,138 @@
+"""GPU parity at the benchmark configurations' full sizes, in the launch
+configuration the benchmark times.  ViT-B/32-shaped: every element against the
+oracle.  The larger stacks are generated on the device; the oracle recomputes
+sampled rows of every layer (first/last rows, tile edges, random rows), which
+is exact because neither the sign masks nor the permutations depend on the row."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from helpers import CODE, compare, cpu_inputs, gather_rows, layers_of, np_lists, to_gpu, to_np
+from paper_2505_11204_amd import binding as rb
+from paper_2505_11204_amd import workloads as wl
+from paper_2505_11204_amd.workloads import Layer
+
+pytestmark = pytest.mark.gpu
+
+TD = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+
+@pytest.fixture(autouse=True)
+def _cleanup():
+    rb.set_tile_rows(0, 0)
+    yield
+    torch.cuda.synchronize()
+    rb.shutdown()
+    torch.cuda.empty_cache()
+
+
+def test_vit_b32_every_element():
+    stack = wl.vit_b32()
+    layers = layers_of(stack)
+    K = 8
+    seeds = [42 + i for i in range(K)]
+    base, deltas = cpu_inputs(stack, K, "f32")
+    gd = [to_gpu(d) for d in deltas]
+    gm = rb.merge(layers, gd, seeds)
+    om = oracle.merge(layers, [np_lists(d) for d in deltas], seeds, n_threads=16)
+    for l in range(len(stack)):
+        compare(gm[l], om[l], "vit-b merged %d" % l)
+    del gd
+    gb = to_gpu(base)
+    nb = np_lists(base)
+    for i in range(K):  # retrieve each task
+        go = rb.retrieve(layers, gm, gb, seeds[i], 1.0)
+        if i in (0, 5):  # the oracle recomputes two of the eight in full ...
+            oo = oracle.retrieve(layers, om, nb, seeds[i], 1.0, n_threads=16)
+            for l in range(len(stack)):
+                compare(go[l], oo[l], "vit-b task %d layer %d" % (i, l))
+        else:            # ... and sampled rows of the others
+            _sampled_retrieve_check(stack, gm, gb, go, seeds[i], 1.0, "f32", "f32", "f32")
+
+
+def _row_sets(stack, n_pick=16):
+    return [wl.shadow_rows(l.rows, n_pick, 99) for l in stack]
+
+
+def _shadow(stack, row_sets):
+    return [(len(r), l.cols, l.group, l.flags) for l, r in zip(stack, row_sets)]
+
+
+def _same_bits(a, b, what):
+    va = a.view(np.uint32 if a.dtype == np.float32 else np.uint16)
+    vb = b.view(np.uint32 if b.dtype == np.float32 else np.uint16)
+    bad = np.nonzero(va.reshape(-1) != vb.reshape(-1))[0]
+    assert bad.size == 0, "%s: %d of %d sampled elements differ" % (what, bad.size, va.size)
+
+
+def _sampled_retrieve_check(stack, gm, gb, go, seed, lam, d_merged, d_base, d_out):
+    rs = _row_sets(stack)
+    sh = _shadow(stack, rs)
+    want = oracle.retrieve(sh, gather_rows(gm, rs), gather_rows(gb, rs), seed, lam,
+                           CODE[d_merged], CODE[d_base], CODE[d_out], n_threads=8)
+    got = gather_rows(go, rs)
+    for l in range(len(stack)):
+        _same_bits(got[l], want[l], "sampled retrieve layer %d" % l)
+
+
+def _sampled_stack_parity(stack, K, dtype, seeds, lam, retrieve_tasks, delta_std, scales=None, deltas=None, base=None):
+    layers = layers_of(stack)
+    if deltas is None:
+        base, deltas = wl.make_inputs(stack, K, dtype=dtype, device="cuda", data_seed=1234,
+                                      delta_std=delta_std, scales=scales)
+    gm = rb.merge(layers, deltas, seeds)
+    torch.cuda.synchronize()
+    rs = _row_sets(stack)
+    sh = _shadow(stack, rs)
+    sh_deltas = [gather_rows(d, rs) for d in deltas]
+    want_m = oracle.merge(sh, sh_deltas, seeds, CODE[dtype], CODE[dtype], n_threads=8)
+    got_m = gather_rows(gm, rs)
+    for l in range(len(stack)):
+        _same_bits(got_m[l], want_m[l], "merged layer %d" % l)
+    out = rb.alloc_like_layers(layers, TD[dtype])
+    sh_base = gather_rows(base, rs)
+    for i in retrieve_tasks:
+        rb.retrieve(layers, gm, base, seeds[i], lam, out=out)
+        torch.cuda.synchronize()
+        want_o = oracle.retrieve(sh, want_m, sh_base, seeds[i], lam, CODE[dtype], CODE[dtype], CODE[dtype], n_threads=8)
+        got_o = gather_rows(out, rs)
+        for l in range(len(stack)):
+            _same_bits(got_o[l], want_o[l], "task %d layer %d" % (i, l))
+    return gm
+
+
+def test_vit_l14_twenty_tasks_sampled_rows():
+    K = 20
+    scales = wl.task_scales(K, 1234)
+    _sampled_stack_parity(wl.vit_l14(), K, "f32", [42 + i for i in range(K)], 1.0, list(range(K)), 1e-3, scales)
+
+
+def test_t5_base_bf16_sampled_rows():
+    _sampled_stack_parity(wl.t5_base(), 8, "bf16", [42 + i for i in range(8)], 1.0, [0, 7], 1e-3)
+
+
+def test_t5_base_lora_variant_sampled_rows():
+    # rank-16 adapters on the q and v projections, materialised on the matrix cores, then merged
+    stack_full = wl.t5_base()
+    targets = wl.t5_lora_targets(stack_full)
+    stack = [stack_full[t] for t in targets]
+    K = 8
+    factors = wl.make_lora_factors(stack, list(range(len(stack))), K, rank=16, dtype="bf16", device="cuda")
+    deltas = []
+    for per in factors:
+        deltas.append(rb.lora_materialize_batched([f[0] for f in per], [f[1] for f in per], 1.0))
+    # the materialised deltas against the float64 oracle, for a sample of matrices
+    for i, t in ((0, 0), (3, 17), (7, 71)):
+        Bq, Aq = factors[i][t]
+        want, mag = oracle.lora(to_np(Bq), to_np(Aq), 1.0, 1)
+        got = deltas[i][t].float().cpu().numpy().astype(np.float64)
+        tol = 16 * 2.0 ** -24 * mag + 2.0 ** -8 * np.abs(want) + 2.0 ** -133
+        assert (np.abs(got - want) <= tol).all()
+    base, _ = wl.make_inputs(stack, 0, dtype="bf16", device="cuda")
+    _sampled_stack_parity(stack, K, "bf16", [42 + i for i in range(K)], 1.0, [2], 1e-3, deltas=deltas, base=base)
+
+
+def test_llama_7b_bf16_sampled_rows():
+    K = 8
+    _sampled_stack_parity(wl.llama_7b(), K, "bf16", [42 + i for i in range(K)], 1.0, [0, 3, 7], 5e-4)

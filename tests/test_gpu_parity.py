@@ -1,0 +1,319 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element
+by element, on the same seeded inputs.  Bar: sign masks, permutations and f32
+outputs bit-exact; bf16 outputs within 1 bf16 ulp (and in fact bit-equal, which
+is asserted too, since both sides round the same binary32 value the same way)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from helpers import CODE, bits_equal, compare, cpu_inputs, layers_of, np_lists, to_gpu, to_np
+from paper_2505_11204_amd import binding as rb
+from paper_2505_11204_amd import workloads as wl
+from paper_2505_11204_amd.workloads import FLIP, SHIFT, SHUFFLE, SRSF, Layer
+
+pytestmark = pytest.mark.gpu
+
+TD = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+
+@pytest.fixture(autouse=True)
+def _default_tiles():
+    rb.set_tile_rows(0, 0)
+    yield
+    torch.cuda.synchronize()
+    rb.set_tile_rows(0, 0)
+
+
+def ragged_stack():
+    """Several tiles per layer at 16 rows per tile, ragged row and column tails,
+    vector and element-wise layers, groups interleaved, singletons."""
+    return [
+        Layer(130, 1032, 0, SRSF), Layer(70, 520, 1, SRSF), Layer(130, 1032, 0, SRSF),
+        Layer(257, 136, -1, FLIP), Layer(70, 520, 1, SRSF), Layer(130, 1032, 0, SRSF),
+        Layer(5, 77, -1, FLIP), Layer(3, 1, -1, FLIP), Layer(1, 3000, -1, FLIP),
+        Layer(33, 2048, 2, SRSF), Layer(33, 2048, 2, SRSF), Layer(19, 130, 3, SHUFFLE),
+        Layer(19, 130, 3, SHUFFLE), Layer(19, 130, 3, SHUFFLE), Layer(64, 4104, -1, 0),
+    ]
+
+
+def run_both(stack, n_tasks, seeds, d_in, d_merged, d_base, d_out, lam, tasks_to_retrieve,
+             data_seed=1234, scales=None):
+    layers = layers_of(stack)
+    base, deltas = cpu_inputs(stack, n_tasks, d_in, data_seed, scales)
+    if d_base != d_in:
+        base = [b.to(TD[d_base]) for b in base]
+    g_merged = rb.merge(layers, [to_gpu(d) for d in deltas], seeds, merged_dtype=TD[d_merged])
+    o_merged = oracle.merge(layers, [np_lists(d) for d in deltas], seeds, CODE[d_in], CODE[d_merged], n_threads=8)
+    for l in range(len(stack)):
+        compare(g_merged[l], o_merged[l], "merged layer %d" % l)
+    g_base = to_gpu(base)
+    for i in tasks_to_retrieve:
+        g_out = rb.retrieve(layers, g_merged, g_base, seeds[i], lam, out_dtype=TD[d_out])
+        o_out = oracle.retrieve(layers, o_merged, np_lists(base), seeds[i], lam,
+                                CODE[d_merged], CODE[d_base], CODE[d_out], n_threads=8)
+        for l in range(len(stack)):
+            compare(g_out[l], o_out[l], "task %d layer %d" % (i, l))
+    return g_merged, o_merged
+
+
+# ------------------------------------------------------------------ generator
+def test_sign_masks_bit_exact():
+    for seed, layer, cols in [(0, 0, 128), (42, 0, 4096), (43, 17, 11008), (2**64 - 1, 225, 32000),
+                              (0x123456789ABCDEF, 3, 1), (7, 1, 77), (7, 2, 129), (44, 9, 100003)]:
+        g = rb.sign_mask(seed, layer, cols).cpu().numpy()
+        assert np.array_equal(g, oracle.sign_mask(seed, layer, cols)), (seed, layer, cols)
+
+
+def test_permutations_bit_exact():
+    for seed in (0, 42, 43, 2**63):
+        for group in (0, 6, 17):
+            for G in (1, 4, 12, 24, 32):
+                assert rb.layer_perm(seed, group, G) == oracle.layer_perm(seed, group, G).tolist()
+
+
+# ------------------------------------------------------------------ the path
+def test_tiny_config():
+    # 4 tasks, 4 f32 matrices of 256 x 256, seeds 0..3, lambda = 1, merge then retrieve task 2
+    run_both(wl.tiny(), 4, [0, 1, 2, 3], "f32", "f32", "f32", "f32", 1.0, [2])
+
+
+@pytest.mark.parametrize("d_in,d_merged,d_base,d_out", [
+    ("f32", "f32", "f32", "f32"), ("bf16", "bf16", "bf16", "bf16"), ("bf16", "f32", "bf16", "bf16"),
+    ("f32", "bf16", "f32", "f32"), ("bf16", "bf16", "f32", "f32"), ("f32", "f32", "bf16", "bf16"),
+    ("bf16", "f32", "f32", "bf16"), ("bf16", "bf16", "bf16", "f32")])
+@pytest.mark.parametrize("n_tasks", [1, 3, 8, 9, 20])
+def test_ragged_stack_all_dtypes(d_in, d_merged, d_base, d_out, n_tasks):
+    rb.set_tile_rows(16, 16)
+    seeds = [42 + i for i in range(n_tasks)]
+    run_both(ragged_stack(), n_tasks, seeds, d_in, d_merged, d_base, d_out, 0.3, [0, n_tasks - 1])
+
+
+@pytest.mark.parametrize("n_tasks", [2, 4, 5, 6, 7])
+def test_every_register_resident_task_count(n_tasks):
+    rb.set_tile_rows(32, 32)
+    seeds = [1000 + 7 * i for i in range(n_tasks)]
+    run_both(ragged_stack(), n_tasks, seeds, "bf16", "bf16", "bf16", "bf16", 1.0, [n_tasks // 2])
+    run_both(ragged_stack(), n_tasks, seeds, "f32", "f32", "f32", "f32", 1.0, [n_tasks // 2])
+
+
+@pytest.mark.parametrize("flags", [0, FLIP, SHUFFLE, SHIFT, FLIP | SHIFT])
+def test_flag_variants(flags):
+    stack = [Layer(40, 264, 0, flags)] * 5 + [Layer(9, 40, -1, flags & FLIP)]
+    run_both(stack, 3, [5, 6, 7], "f32", "f32", "f32", "f32", 0.7, [1])
+    run_both(stack, 3, [5, 6, 7], "bf16", "bf16", "bf16", "bf16", 0.7, [1])
+
+
+def test_skip_rate_pattern():
+    # only every 2nd layer of the repeated set is shuffled and flipped
+    stack = [Layer(24, 256, 0, SRSF if k % 2 == 0 else 0) for k in range(8)]
+    run_both(stack, 4, [42, 43, 44, 45], "f32", "f32", "f32", "f32", 1.0, [3])
+
+
+@pytest.mark.parametrize("lam", [0.0, 0.1, 1.0, 2.0, -0.5])
+def test_lambda_values(lam):
+    stack = [Layer(20, 512, 0, SRSF)] * 3
+    run_both(stack, 4, [1, 2, 3, 4], "f32", "f32", "f32", "f32", lam, [2])
+    run_both(stack, 4, [1, 2, 3, 4], "bf16", "bf16", "bf16", "bf16", lam, [2])
+
+
+def test_single_model_round_trip_is_exact_on_gpu():
+    stack = [Layer(64, 1024, 0, SRSF)] * 4
+    layers = layers_of(stack)
+    base, deltas = cpu_inputs(stack, 1, "f32")
+    gm = rb.merge(layers, [to_gpu(deltas[0])], [9])
+    out = rb.retrieve(layers, gm, to_gpu(base), 9, 1.0)
+    for l in range(4):
+        assert torch.equal(out[l].cpu(), base[l] + deltas[0][l])
+
+
+def test_launch_geometry_does_not_change_results():
+    stack = ragged_stack()
+    layers = layers_of(stack)
+    base, deltas = cpu_inputs(stack, 8, "bf16")
+    gd = [to_gpu(d) for d in deltas]
+    gb = to_gpu(base)
+    seeds = list(range(42, 50))
+    ref_m = ref_o = None
+    for tr in (1, 7, 16, 128, 1000):
+        rb.set_tile_rows(tr, tr)
+        m = rb.merge(layers, gd, seeds)
+        o = rb.retrieve(layers, m, gb, seeds[3], 0.9)
+        torch.cuda.synchronize()
+        if ref_m is None:
+            ref_m, ref_o = m, o
+        else:
+            for l in range(len(stack)):
+                assert torch.equal(m[l].view(torch.int16), ref_m[l].view(torch.int16))
+                assert torch.equal(o[l].view(torch.int16), ref_o[l].view(torch.int16))
+
+
+def test_unaligned_layers_take_the_elementwise_path_with_equal_results():
+    stack = [Layer(10, 264, 0, SRSF)] * 3
+    layers = layers_of(stack)
+    base, deltas = cpu_inputs(stack, 2, "f32")
+    seeds = [3, 4]
+
+    def shifted(t):  # same values at a 4-byte offset: not 16-byte aligned
+        buf = torch.empty(t.numel() + 1, dtype=t.dtype, device="cuda")
+        v = buf[1:].view(t.shape)
+        v.copy_(t)
+        return v
+    gd = [[shifted(t) for t in d] for d in deltas]
+    assert gd[0][0].data_ptr() % 16 != 0
+    m = rb.merge(layers, gd, seeds)
+    o_m = oracle.merge(layers, [np_lists(d) for d in deltas], seeds)
+    for l in range(3):
+        compare(m[l], o_m[l], "unaligned merge %d" % l)
+    out = rb.retrieve(layers, m, [shifted(b) for b in base], 4, 1.0)
+    o_out = oracle.retrieve(layers, o_m, np_lists(base), 4, 1.0)
+    for l in range(3):
+        compare(out[l], o_out[l], "unaligned retrieve %d" % l)
+
+
+def test_in_place_retrieve_into_base():
+    stack = [Layer(48, 512, 0, SRSF)] * 4
+    layers = layers_of(stack)
+    base, deltas = cpu_inputs(stack, 3, "bf16")
+    seeds = [1, 2, 3]
+    m = rb.merge(layers, [to_gpu(d) for d in deltas], seeds)
+    gb = to_gpu(base)
+    rb.retrieve(layers, m, gb, 2, 1.0, out=gb)
+    o_m = oracle.merge(layers, [np_lists(d) for d in deltas], seeds, 1, 1)
+    o_out = oracle.retrieve(layers, o_m, np_lists(base), 2, 1.0, 1, 1, 1)
+    for l in range(4):
+        compare(gb[l], o_out[l], "in-place %d" % l)
+
+
+def test_special_values():
+    # signed zeros, denormals, infinities, large magnitudes; NaN positions must agree
+    stack = [Layer(4, 256, -1, FLIP)]
+    layers = layers_of(stack)
+    g = torch.Generator().manual_seed(5)
+    K = 3
+    deltas = []
+    specials = torch.tensor([0.0, -0.0, 1e-45, -1e-45, 1e-39, 3e38, -3e38, float("inf"), float("-inf"),
+                             float("nan"), 1.0, -1.0, 65504.0, 2.0 ** -126, 1.1754942e-38, 7.0])
+    for i in range(K):
+        x = torch.randn(4, 256, generator=g)
+        idx = torch.randint(0, 16, (4, 256), generator=g)
+        pick = torch.rand(4, 256, generator=g) < 0.5
+        x = torch.where(pick, specials[idx], x)
+        deltas.append([x])
+    base = [torch.randn(4, 256, generator=g)]
+    seeds = [11, 12, 13]
+    for dt in ("f32", "bf16"):
+        dd = [[t.to(TD[dt]) for t in d] for d in deltas]
+        bb = [b.to(TD[dt]) for b in base]
+        m = rb.merge(layers, [to_gpu(d) for d in dd], seeds)
+        o_m = oracle.merge(layers, [np_lists(d) for d in dd], seeds, CODE[dt], CODE[dt])
+        out = rb.retrieve(layers, m, to_gpu(bb), 12, 0.5)
+        o_out = oracle.retrieve(layers, o_m, np_lists(bb), 12, 0.5, CODE[dt], CODE[dt], CODE[dt])
+        for got, want in ((m[0], o_m[0]), (out[0], o_out[0])):
+            gf = got.float().cpu().numpy()
+            wf = oracle.bf16_to_f32(want) if dt == "bf16" else want
+            assert np.array_equal(np.isnan(gf), np.isnan(wf))
+            ok = ~np.isnan(wf)
+            gb_, wb_ = to_np(got)[ok], np.asarray(want)[ok]
+            assert np.array_equal(gb_.view(np.uint32 if dt == "f32" else np.uint16),
+                                  wb_.view(np.uint32 if dt == "f32" else np.uint16))
+
+
+def test_empty_and_invalid_requests_are_rejected():
+    stack = [Layer(8, 256, 0, SRSF)] * 2
+    layers = layers_of(stack)
+    base, deltas = cpu_inputs(stack, 2, "f32")
+    gd = [to_gpu(d) for d in deltas]
+    with pytest.raises(rb.RandesError):
+        rb.merge(layers, gd, [1, 2], merged=gd[0])          # output aliases an input
+    m = rb.merge(layers, gd, [1, 2])
+    with pytest.raises(rb.RandesError):
+        rb.retrieve(layers, m, to_gpu(base), 1, 1.0, out=m)  # out aliases the superposition
+    with pytest.raises(rb.RandesError):
+        rb.retrieve(layers, m, to_gpu(base), 1, float("nan"))
+    with pytest.raises(rb.RandesError):
+        rb.merge([(8, 256, 0, 3), (4, 512, 0, 3)], gd, [1, 2])  # group with mixed shapes
+    with pytest.raises(ValueError):
+        rb.merge(layers, [], [])                               # no models
+
+
+# ------------------------------------------------------------------ hot swap
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_hot_swap(dt):
+    stack = ragged_stack()
+    layers = layers_of(stack)
+    _, deltas = cpu_inputs(stack, 4, dt)
+    seeds = [10, 11, 12, 13]
+    gd = [to_gpu(d) for d in deltas]
+    part = rb.merge(layers, gd[:3], seeds[:3])
+    rb.update(layers, part, gd[3], seeds[3])
+    o_part = oracle.merge(layers, [np_lists(d) for d in deltas[:3]], seeds[:3], CODE[dt], CODE[dt])
+    oracle.update(layers, o_part, np_lists(deltas[3]), seeds[3], False, CODE[dt], CODE[dt])
+    for l in range(len(stack)):
+        compare(part[l], o_part[l], "hot add %d" % l)
+    if dt == "f32":  # appending keeps the summation order: identical to a fresh merge of all four
+        fresh = rb.merge(layers, gd, seeds)
+        for l in range(len(stack)):
+            assert torch.equal(part[l].view(torch.int32), fresh[l].view(torch.int32))
+    rb.update(layers, part, gd[1], seeds[1], remove=True)
+    oracle.update(layers, o_part, np_lists(deltas[1]), seeds[1], True, CODE[dt], CODE[dt])
+    for l in range(len(stack)):
+        compare(part[l], o_part[l], "hot remove %d" % l)
+
+
+# ------------------------------------------------------------------ LoRA
+@pytest.mark.parametrize("dt_ab,dt_out", [("bf16", "bf16"), ("bf16", "f32"), ("f32", "f32"), ("f32", "bf16")])
+@pytest.mark.parametrize("rows,cols,rank", [(768, 768, 16), (70, 100, 16), (33, 129, 5), (64, 256, 40), (1, 1, 1)])
+def test_lora_materialize(dt_ab, dt_out, rows, cols, rank):
+    g = torch.Generator().manual_seed(rows * 1000 + cols + rank)
+    B = (torch.randn(rows, rank, generator=g) * 0.01).to(TD[dt_ab])
+    A = (torch.randn(rank, cols, generator=g) * 0.01).to(TD[dt_ab])
+    scale = 2.0
+    got = rb.lora_materialize(B.cuda(), A.cuda(), scale, out_dtype=TD[dt_out]).float().cpu().numpy().astype(np.float64)
+    want, mag = oracle.lora(to_np(B), to_np(A), scale, CODE[dt_ab])
+    # binary32 accumulation in any order: rank * 2^-24 * sum|B||A|; one more rounding for the
+    # scale multiply; half a bf16 ulp (2^-9 relative) if the output is bf16
+    tol = rank * 2.0 ** -24 * mag + 2.0 ** -23 * np.abs(want) + 1e-45
+    if dt_out == "bf16":
+        tol = tol + 2.0 ** -8 * np.abs(want) + 2.0 ** -133
+    err = np.abs(got - want)
+    assert (err <= tol).all(), (err.max(), tol[err > tol].min() if (err > tol).any() else None)
+
+
+def test_lora_exact_cases_and_batched():
+    # power-of-two valued factors: every product and partial sum is exact, so any order agrees exactly
+    g = torch.Generator().manual_seed(3)
+    B = (2.0 ** torch.randint(-3, 4, (96, 16), generator=g).float()) * (torch.randint(0, 2, (96, 16), generator=g) * 2 - 1)
+    A = (2.0 ** torch.randint(-3, 4, (16, 160), generator=g).float()) * (torch.randint(0, 2, (16, 160), generator=g) * 2 - 1)
+    want, _ = oracle.lora(B.numpy(), A.numpy(), 1.0, 0)
+    for dt in ("bf16", "f32"):
+        got = rb.lora_materialize(B.to(TD[dt]).cuda(), A.to(TD[dt]).cuda(), 1.0, out_dtype=torch.float32)
+        assert np.array_equal(got.cpu().numpy().astype(np.float64), want)
+    # identity-padded B copies A
+    Bi = torch.zeros(40, 16)
+    Bi[:16] = torch.eye(16)
+    Ar = torch.randn(16, 72, generator=g).to(torch.bfloat16)
+    got = rb.lora_materialize(Bi.to(torch.bfloat16).cuda(), Ar.cuda(), 1.0)
+    assert torch.equal(got[:16].cpu(), Ar) and (got[16:] == 0).all()
+    # batched = one by one
+    Bs = [(torch.randn(r, 16, generator=g) * 0.01).to(torch.bfloat16).cuda() for r in (64, 70, 768)]
+    As = [(torch.randn(16, c, generator=g) * 0.01).to(torch.bfloat16).cuda() for c in (128, 100, 768)]
+    outs = rb.lora_materialize_batched(Bs, As, 0.5)
+    for Bq, Aq, o in zip(Bs, As, outs):
+        single = rb.lora_materialize(Bq, Aq, 0.5)
+        assert torch.equal(o.view(torch.int16), single.view(torch.int16))
+
+
+def test_lora_deltas_feed_the_merge_bit_exactly():
+    # the GPU-materialised deltas are copied to the host and given to the oracle's merge,
+    # so the merge itself stays bit-exact although B.A is only tolerance-checked
+    stack = [Layer(768, 768, 0, SRSF)] * 3
+    layers = layers_of(stack)
+    K = 3
+    factors = wl.make_lora_factors(stack, [0, 1, 2], K, rank=16, dtype="bf16", device="cuda")
+    deltas = [[rb.lora_materialize(Bq, Aq, 1.0) for (Bq, Aq) in per] for per in factors]
+    seeds = [42, 43, 44]
+    m = rb.merge(layers, deltas, seeds)
+    o_m = oracle.merge(layers, [[to_np(t) for t in per] for per in deltas], seeds, 1, 1, n_threads=8)
+    for l in range(3):
+        compare(m[l], o_m[l], "lora merge %d" % l)

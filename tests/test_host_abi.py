@@ -1,0 +1,113 @@
+"""CPU-only checks of the GPU library's host side: it loads, exports what the
+header declares, its host-only entry points agree with the oracle, and bad
+arguments come back as error codes before any GPU work."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import oracle
+from paper_2505_11204_amd import binding as rb
+from paper_2505_11204_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(rb.LIB_PATH):
+        from paper_2505_11204_amd import build
+        build.build(force=True)
+    return rb.lib()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "randes.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(randes_[a-z_]+)\s*\(", header))
+    assert declared == set(rb.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_layer_perm_matches_oracle(lib):
+    for seed in (0, 1, 42, 43, 2**64 - 1, 0x299F31D0A4093822):
+        for group in (0, 1, 10):
+            for G in (1, 2, 4, 12, 24, 32, 77):
+                assert rb.layer_perm(seed, group, G) == oracle.layer_perm(seed, group, G).tolist()
+
+
+@pytest.mark.parametrize("name", ["tiny", "vit_b32", "vit_l14", "t5_base", "llama_7b"])
+def test_source_table_matches_oracle_on_the_benchmark_stacks(lib, name):
+    stack = wl.STACKS[name]()
+    layers = [(l.rows, l.cols, l.group, l.flags) for l in stack]
+    for seed in (42, 49):
+        want = oracle.source_table(layers, [seed])[0].tolist()
+        assert rb.source_table(layers, seed) == want
+        assert sorted(want) == list(range(len(layers)))
+        for l, s in enumerate(want):  # only same-shape, same-group layers trade places
+            assert layers[l][:3] == layers[s][:3]
+
+
+def test_source_table_skip_rate_and_shift(lib):
+    layers = [(1, 4, 0, (wl.SRSF if k % 2 == 0 else 0)) for k in range(8)] + [(1, 4, 3, wl.SHIFT)] * 5
+    want = oracle.source_table(layers, [5])[0].tolist()
+    assert rb.source_table(layers, 5) == want
+    assert want[8:] == [12, 8, 9, 10, 11]
+
+
+def test_stack_sizes():
+    assert wl.n_elements(wl.tiny()) == 262144
+    assert wl.n_elements(wl.vit_b32()) == 84934656
+    assert wl.n_elements(wl.vit_l14()) == 301989888
+    assert wl.n_elements(wl.t5_base()) == 247529472
+    assert wl.n_elements(wl.llama_7b()) == 6738149376
+    assert len(wl.t5_lora_targets(wl.t5_base())) == 72
+
+
+def _code(fn, *args):
+    return fn(*args)
+
+
+def test_bad_arguments_are_error_codes_not_crashes(lib):
+    L = rb._Layer
+    one = (L * 1)(L(4, 4, 0, 3))
+    ptr = (ctypes.c_void_p * 1)(0x1000)
+    null = (ctypes.c_void_p * 1)(None)
+    seeds = (ctypes.c_uint64 * 1)(1)
+    EINVAL, ENOTSUP = -1, -2
+    # merge
+    assert lib.randes_merge(None, 1, ptr, 1, seeds, 0, ptr, 0, None) == EINVAL
+    assert lib.randes_merge(one, 0, ptr, 1, seeds, 0, ptr, 0, None) == EINVAL
+    assert lib.randes_merge(one, 1, ptr, 0, seeds, 0, ptr, 0, None) == EINVAL
+    assert lib.randes_merge(one, 1, ptr, rb.MAX_TASKS + 1, seeds, 0, ptr, 0, None) == ENOTSUP
+    assert lib.randes_merge(one, 1, ptr, 1, seeds, 7, ptr, 0, None) == EINVAL
+    assert lib.randes_merge(one, 1, null, 1, seeds, 0, ptr, 0, None) == EINVAL
+    assert lib.randes_merge(one, 1, ptr, 1, None, 0, ptr, 0, None) == EINVAL
+    bad_rows = (L * 1)(L(0, 4, 0, 3))
+    assert lib.randes_merge(bad_rows, 1, ptr, 1, seeds, 0, ptr, 0, None) == EINVAL
+    bad_flag = (L * 1)(L(4, 4, 0, 64))
+    assert lib.randes_merge(bad_flag, 1, ptr, 1, seeds, 0, ptr, 0, None) == EINVAL
+    assert b"flag" in lib.randes_strerror(EINVAL)
+    # retrieve: non-finite lambda
+    assert lib.randes_retrieve(one, 1, ptr, 0, ptr, 0, 1, ctypes.c_float(float("nan")), ptr, 0, None) == EINVAL
+    assert lib.randes_retrieve(one, 1, ptr, 0, ptr, 0, 1, ctypes.c_float(float("inf")), ptr, 0, None) == EINVAL
+    assert lib.randes_retrieve(one, 1, ptr, 0, None, 0, 1, ctypes.c_float(1.0), ptr, 0, None) == EINVAL
+    # mismatched group shapes
+    two = (L * 2)(L(4, 4, 0, 3), L(4, 8, 0, 3))
+    out = (ctypes.c_int32 * 2)()
+    assert lib.randes_source_table(two, 2, 1, out) == EINVAL
+    assert b"shape" in lib.randes_strerror(EINVAL)
+    # perm / mask / lora / knobs
+    assert lib.randes_layer_perm(1, 0, 0, out) == EINVAL
+    assert lib.randes_layer_perm(1, 0, 2, None) == EINVAL
+    assert lib.randes_sign_mask(1, 0, 0, ptr, None) == EINVAL
+    assert lib.randes_sign_mask(1, 0, 16, None, None) == EINVAL
+    assert lib.randes_lora_materialize(None, ptr, 4, 4, 2, ctypes.c_float(1.0), 0, ptr, 0, None) == EINVAL
+    assert lib.randes_lora_materialize(ptr, ptr, 4, 4, 0, ctypes.c_float(1.0), 0, ptr, 0, None) == EINVAL
+    assert lib.randes_update(one, 1, ptr, 0, None, 0, 1, 0, None) == EINVAL
+    assert lib.randes_set_tile_rows(-1, 0) == EINVAL
+    assert lib.randes_set_tile_rows(0, 0) == 0
+    assert lib.randes_strerror(0) == b"ok"
+    assert lib.randes_shutdown() == 0
