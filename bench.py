@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--merge-rows", type=int, default=0, help="rows per merge tile (0 = library default)")
     ap.add_argument("--retrieve-rows", type=int, default=0, help="rows per retrieve tile (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain 4 GiB device copy (torch.mul(src, 1.0, out=dst)) three times, so that HBM byte "
+                         "counters collected over this command can be scaled by a kernel of known traffic")
     ap.add_argument("--cpu-sample-rows", type=int, default=1024)
     return ap.parse_args()
 
@@ -142,6 +145,14 @@ def main():
             if events is not None:
                 b = torch.cuda.Event(enable_timing=True); b.record()
                 events["retrieve"].append((a, b))
+
+    if args.calibration_copy:
+        src = torch.empty(1 << 30, dtype=torch.float32, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
