@@ -164,9 +164,15 @@ const char *randes_strerror(int code);
  * synchronised all streams that ran library work.  Safe to call repeatedly. */
 int randes_shutdown(void);
 
-/* Launch-shape knobs for measurement (rows per tile, 0 = built-in default).
- * Results never depend on them.  Returns RANDES_EINVAL for unusable values. */
+/* Launch-shape knobs for measurement: rows of a tile that one wavefront owns
+ * (0 = built-in default, the kernels' burst size; larger values are clamped to
+ * it).  Results never depend on them.  Returns RANDES_EINVAL for negative values. */
 int randes_set_tile_rows(int32_t merge_rows, int32_t retrieve_rows);
+
+/* Second launch-shape knob: how many of a workgroup's 4 wavefronts may sit side by
+ * side along the columns (4, 2 or 1; 0 = default 4); the rest stack along the rows.
+ * Results never depend on it. */
+int randes_set_tile_cols(int32_t max_waves_along_columns);
 
 #ifdef __cplusplus
 }

@@ -25,7 +25,7 @@ LIB_PATH = os.path.join(_HERE, "librandes.so")
 EXPORTS = ["randes_layer_perm", "randes_source_table", "randes_sign_mask", "randes_merge",
            "randes_retrieve", "randes_update", "randes_lora_materialize",
            "randes_lora_materialize_batched", "randes_strerror", "randes_shutdown",
-           "randes_set_tile_rows"]
+           "randes_set_tile_rows", "randes_set_tile_cols"]
 
 
 class RandesError(RuntimeError):
@@ -67,6 +67,7 @@ def lib():
     L.randes_strerror.restype = ctypes.c_char_p
     L.randes_shutdown.argtypes = []
     L.randes_set_tile_rows.argtypes = [i32, i32]
+    L.randes_set_tile_cols.argtypes = [i32]
     for name in EXPORTS:
         if name != "randes_strerror":
             getattr(L, name).restype = ctypes.c_int
@@ -273,6 +274,11 @@ def lora_materialize_batched(Bs, As, scale=1.0, outs=None, out_dtype=None, strea
 def set_tile_rows(merge_rows=0, retrieve_rows=0):
     """Launch-shape knob for measurements (0 = default).  Results do not depend on it."""
     _check(lib().randes_set_tile_rows(int(merge_rows), int(retrieve_rows)))
+
+
+def set_tile_cols(max_waves_along_columns=0):
+    """Second launch-shape knob (4, 2, 1; 0 = default).  Results do not depend on it."""
+    _check(lib().randes_set_tile_cols(int(max_waves_along_columns)))
 
 
 def shutdown():

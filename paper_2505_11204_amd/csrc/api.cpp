@@ -37,7 +37,11 @@ bool dtype_ok(int d) { return d == RANDES_F32 || d == RANDES_BF16; }
 size_t elem_bytes(int d) { return d == RANDES_F32 ? 4 : 2; }
 bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
-int g_merge_rows = 128, g_retrieve_rows = 128;
+int g_merge_rows = 0, g_retrieve_rows = 0;   // rows per wave per tile; 0 = the kernels' burst size
+int g_max_wx_shift = 2;   // widest tile: 4 waves side by side along the columns
+
+// A wave handles one burst of at most `burst` rows; the knob can only shrink it.
+int clamp_rows(int knob, int burst) { return (knob <= 0 || knob > burst) ? burst : knob; }
 
 // ------------------------------------------------------------------ plan cache
 struct CachedPlan {
@@ -65,15 +69,18 @@ CachedPlan *lookup(const std::string &key, int device)
 }
 
 // Lay the host plan out in one blob, upload it, and fill the kernel arguments.
-int upload(const HostPlan &hp, int n_tasks, CachedPlan *cp)
+int upload(HostPlan &hp, int n_tasks, CachedPlan *cp)
 {
     auto pad = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    build_coarse_index(&hp.vec);
+    build_coarse_index(&hp.scl);
     const SubPlan *sub[2] = { &hp.vec, &hp.scl };
-    size_t off_layers[2], off_srcs[2], off_tb[2], off = 0;
+    size_t off_layers[2], off_srcs[2], off_tb[2], off_co[2], off = 0;
     for (int s = 0; s < 2; ++s) {
         off_layers[s] = off; off = pad(off + sub[s]->layers.size() * sizeof(LayerDev));
         off_srcs[s] = off;   off = pad(off + sub[s]->srcs.size() * sizeof(void *));
         off_tb[s] = off;     off = pad(off + sub[s]->tile_begin.size() * sizeof(uint32_t));
+        off_co[s] = off;     off = pad(off + sub[s]->coarse.size() * sizeof(uint32_t));
     }
     const size_t off_keys = off;
     off = pad(off + hp.keys.size() * sizeof(uint32_t));
@@ -82,6 +89,7 @@ int upload(const HostPlan &hp, int n_tasks, CachedPlan *cp)
         if (!sub[s]->layers.empty()) memcpy(host.data() + off_layers[s], sub[s]->layers.data(), sub[s]->layers.size() * sizeof(LayerDev));
         if (!sub[s]->srcs.empty()) memcpy(host.data() + off_srcs[s], sub[s]->srcs.data(), sub[s]->srcs.size() * sizeof(void *));
         if (!sub[s]->tile_begin.empty()) memcpy(host.data() + off_tb[s], sub[s]->tile_begin.data(), sub[s]->tile_begin.size() * sizeof(uint32_t));
+        memcpy(host.data() + off_co[s], sub[s]->coarse.data(), sub[s]->coarse.size() * sizeof(uint32_t));
     }
     if (!hp.keys.empty()) memcpy(host.data() + off_keys, hp.keys.data(), hp.keys.size() * sizeof(uint32_t));
     hipError_t e = hipMalloc(&cp->blob, off);
@@ -96,6 +104,7 @@ int upload(const HostPlan &hp, int n_tasks, CachedPlan *cp)
         a.layers = (const LayerDev *)(b + off_layers[s]);
         a.srcs = (const void *const *)(b + off_srcs[s]);
         a.tile_begin = (const uint32_t *)(b + off_tb[s]);
+        a.coarse = (const uint32_t *)(b + off_co[s]);
         a.keys = (const uint32_t *)(b + off_keys);
         a.n_layers = (int32_t)sub[s]->layers.size();
         a.n_tasks = n_tasks;
@@ -105,10 +114,10 @@ int upload(const HostPlan &hp, int n_tasks, CachedPlan *cp)
 }
 
 // Add one slot layer to the vector or element-wise sub-plan.
-int place(HostPlan *hp, LayerDev d, const void *const *srcs, int n_srcs, bool vector_ok, int vec, int tile_rows)
+int place(HostPlan *hp, LayerDev d, const void *const *srcs, int n_srcs, bool vector_ok, int vec, int rows_per_wave)
 {
     SubPlan &sp = vector_ok ? hp->vec : hp->scl;
-    const uint64_t tiles = plan_layer_geometry(&d, vector_ok ? vec : 1, tile_rows);
+    const uint64_t tiles = plan_layer_geometry(&d, vector_ok ? vec : 1, rows_per_wave, g_max_wx_shift);
     if (tiles == 0) return fail(RANDES_ENOTSUP, "layer too wide for 32-bit in-tile offsets");
     if ((uint64_t)sp.n_tiles + tiles >= ((uint64_t)1 << 31)) return fail(RANDES_ENOTSUP, "too many tiles for one launch");
     if (sp.tile_begin.empty()) sp.tile_begin.push_back(0);
@@ -202,7 +211,7 @@ int randes_merge(const randes_layer *layers, int32_t n_layers,
 
     int dev;
     if ((rc = current_device(&dev))) return rc;
-    const int32_t tile_rows = g_merge_rows;
+    const int32_t tile_rows = g_merge_rows * 4 + g_max_wx_shift;   // both knobs, for the cache key
     std::string key;
     const int32_t head[6] = { PLAN_MERGE, n_layers, n_tasks, (int32_t)delta_dtype, (int32_t)merged_dtype, tile_rows };
     append(&key, head, sizeof(head));
@@ -248,7 +257,7 @@ int randes_merge(const randes_layer *layers, int32_t n_layers,
                 ptrs[(size_t)i] = deltas[(size_t)i * n_layers + src[(size_t)i][(size_t)l]];
                 vector_ok = vector_ok && aligned16(ptrs[(size_t)i]);
             }
-            if ((rc = place(&hp, d, ptrs.data(), n_tasks, vector_ok, vec, tile_rows))) return rc;
+            if ((rc = place(&hp, d, ptrs.data(), n_tasks, vector_ok, vec, clamp_rows(g_merge_rows, merge_burst_rows())))) return rc;
         }
         CachedPlan fresh;
         fresh.key = key;
@@ -281,7 +290,7 @@ int randes_retrieve(const randes_layer *layers, int32_t n_layers,
 
     int dev;
     if ((rc = current_device(&dev))) return rc;
-    const int32_t tile_rows = g_retrieve_rows;
+    const int32_t tile_rows = g_retrieve_rows * 4 + g_max_wx_shift;   // both knobs, for the cache key
     std::string key;
     const int32_t head[6] = { PLAN_RETRIEVE, n_layers, (int32_t)merged_dtype, (int32_t)base_dtype, (int32_t)out_dtype, tile_rows };
     append(&key, head, sizeof(head));
@@ -323,7 +332,7 @@ int randes_retrieve(const randes_layer *layers, int32_t n_layers,
             d.layer_id = (uint32_t)l;
             d.flip = (layers[l].flags & RANDES_FLIP) ? 1u : 0u;
             const bool vector_ok = (layers[l].cols % vec) == 0 && aligned16(d.dst) && aligned16(d.a) && aligned16(d.b);
-            if ((rc = place(&hp, d, nullptr, 0, vector_ok, vec, tile_rows))) return rc;
+            if ((rc = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(g_retrieve_rows, two_input_burst_rows())))) return rc;
         }
         CachedPlan fresh;
         fresh.key = key;
@@ -358,7 +367,7 @@ int randes_update(const randes_layer *layers, int32_t n_layers,
 
     int dev;
     if ((rc = current_device(&dev))) return rc;
-    const int32_t tile_rows = g_retrieve_rows;
+    const int32_t tile_rows = g_retrieve_rows * 4 + g_max_wx_shift;   // both knobs, for the cache key
     std::string key;
     const int32_t head[5] = { PLAN_UPDATE, n_layers, (int32_t)merged_dtype, (int32_t)delta_dtype, tile_rows };
     append(&key, head, sizeof(head));
@@ -391,7 +400,7 @@ int randes_update(const randes_layer *layers, int32_t n_layers,
             d.layer_id = (uint32_t)l;
             d.flip = (layers[l].flags & RANDES_FLIP) ? 1u : 0u;
             const bool vector_ok = (layers[l].cols % vec) == 0 && aligned16(d.dst) && aligned16(d.a);
-            if ((rc = place(&hp, d, nullptr, 0, vector_ok, vec, tile_rows))) return rc;
+            if ((rc = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(g_retrieve_rows, two_input_burst_rows())))) return rc;
         }
         CachedPlan fresh;
         fresh.key = key;
@@ -496,8 +505,22 @@ int randes_set_tile_rows(int32_t merge_rows, int32_t retrieve_rows)
     if (merge_rows < 0 || retrieve_rows < 0 || merge_rows > (1 << 20) || retrieve_rows > (1 << 20))
         return fail(RANDES_EINVAL, "tile rows out of range");
     std::lock_guard<std::mutex> lock(g_mu);
-    g_merge_rows = merge_rows ? merge_rows : 128;
-    g_retrieve_rows = retrieve_rows ? retrieve_rows : 128;
+    g_merge_rows = merge_rows;
+    g_retrieve_rows = retrieve_rows;
+    return RANDES_OK;
+}
+
+int randes_set_tile_cols(int32_t max_waves_along_columns)
+{
+    int shift;
+    switch (max_waves_along_columns) {
+    case 0: case 4: shift = 2; break;
+    case 2: shift = 1; break;
+    case 1: shift = 0; break;
+    default: return fail(RANDES_EINVAL, "max_waves_along_columns must be 0, 1, 2 or 4");
+    }
+    std::lock_guard<std::mutex> lock(g_mu);
+    g_max_wx_shift = shift;
     return RANDES_OK;
 }
 

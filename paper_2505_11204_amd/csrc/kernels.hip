@@ -19,11 +19,27 @@ namespace randes {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
+// Layer pointers reach the kernels through tables in memory, so the compiler cannot tell that
+// they point to global memory and would fall back to flat addressing; say so explicitly.
+#define RANDES_GLOBAL __attribute__((address_space(1)))
+typedef const RANDES_GLOBAL char *gcptr;   // read-only global bytes
+typedef RANDES_GLOBAL char *gptr;          // writable global bytes
+
 constexpr int WG = 256;          // threads per workgroup
 constexpr int WAVES = WG / 64;
 constexpr int KREG_MAX = 8;      // merge: up to this many tasks keep their masks in registers
-constexpr int MERGE_U = 2;       // merge: rows in flight per wave
-constexpr int RETR_U = 4;        // retrieve / update: rows in flight per wave
+#ifndef RANDES_MERGE_R
+#define RANDES_MERGE_R 4
+#endif
+#ifndef RANDES_TWO_INPUT_R
+#define RANDES_TWO_INPUT_R 8
+#endif
+#ifndef RANDES_STORE_AT_END
+#define RANDES_STORE_AT_END 1
+#endif
+constexpr bool STORE_AT_END = RANDES_STORE_AT_END != 0;   // hold a burst's results until all of them exist
+constexpr int MERGE_R = RANDES_MERGE_R;          // merge: rows a wave loads before it stores (one burst)
+constexpr int TWO_INPUT_R = RANDES_TWO_INPUT_R;  // retrieve / update: the same
 
 __device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }
 __device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
@@ -43,19 +59,19 @@ template <int DT, int VEC> struct NumWords {
 
 // Load VEC elements of dtype DT from byte address p as raw dwords (bf16 stays packed).
 template <int DT, int VEC>
-__device__ __forceinline__ void load_raw(const char *p, uint32_t (&raw)[NumWords<DT, VEC>::value])
+__device__ __forceinline__ void load_raw(gcptr p, uint32_t (&raw)[NumWords<DT, VEC>::value])
 {
     constexpr int NW = NumWords<DT, VEC>::value;
     if constexpr (NW == 1) {
-        if constexpr (DT == DT_F32) raw[0] = __builtin_nontemporal_load((const uint32_t *)p);
-        else raw[0] = (uint32_t)__builtin_nontemporal_load((const uint16_t *)p);
+        if constexpr (DT == DT_F32) raw[0] = __builtin_nontemporal_load((const RANDES_GLOBAL uint32_t *)p);
+        else raw[0] = (uint32_t)__builtin_nontemporal_load((const RANDES_GLOBAL uint16_t *)p);
     } else if constexpr (NW == 2) {
-        const u32x2 q = __builtin_nontemporal_load((const u32x2 *)p);
+        const u32x2 q = __builtin_nontemporal_load((const RANDES_GLOBAL u32x2 *)p);
         raw[0] = q.x; raw[1] = q.y;
     } else {
 #pragma unroll
         for (int h = 0; h < NW / 4; ++h) {
-            const u32x4 q = __builtin_nontemporal_load((const u32x4 *)p + h);
+            const u32x4 q = __builtin_nontemporal_load((const RANDES_GLOBAL u32x4 *)p + h);
             raw[4 * h + 0] = q.x; raw[4 * h + 1] = q.y; raw[4 * h + 2] = q.z; raw[4 * h + 3] = q.w;
         }
     }
@@ -75,40 +91,6 @@ __device__ __forceinline__ void widen(const uint32_t (&raw)[NumWords<DT, VEC>::v
         for (int j = 0; j < VEC / 2; ++j) {
             v[2 * j] = u2f(raw[j] << 16);
             v[2 * j + 1] = u2f(raw[j] & 0xffff0000u);
-        }
-    }
-}
-
-// Store VEC binary32 values as dtype DT at byte address p.
-template <int DT, int VEC>
-__device__ __forceinline__ void store_vec(char *p, const float (&v)[VEC])
-{
-    if constexpr (DT == DT_F32) {
-        if constexpr (VEC == 1) {
-            __builtin_nontemporal_store(v[0], (float *)p);
-        } else {
-#pragma unroll
-            for (int h = 0; h < VEC / 4; ++h) {
-                u32x4 q;
-                q.x = f2u(v[4 * h]); q.y = f2u(v[4 * h + 1]); q.z = f2u(v[4 * h + 2]); q.w = f2u(v[4 * h + 3]);
-                __builtin_nontemporal_store(q, (u32x4 *)p + h);
-            }
-        }
-    } else {
-        if constexpr (VEC == 1) {
-            __builtin_nontemporal_store((uint16_t)bf16_rne(v[0]), (uint16_t *)p);
-        } else if constexpr (VEC == 4) {
-            u32x2 q;
-            q.x = bf16_rne(v[0]) | (bf16_rne(v[1]) << 16);
-            q.y = bf16_rne(v[2]) | (bf16_rne(v[3]) << 16);
-            __builtin_nontemporal_store(q, (u32x2 *)p);
-        } else {
-            u32x4 q;
-            q.x = bf16_rne(v[0]) | (bf16_rne(v[1]) << 16);
-            q.y = bf16_rne(v[2]) | (bf16_rne(v[3]) << 16);
-            q.z = bf16_rne(v[4]) | (bf16_rne(v[5]) << 16);
-            q.w = bf16_rne(v[6]) | (bf16_rne(v[7]) << 16);
-            __builtin_nontemporal_store(q, (u32x4 *)p);
         }
     }
 }
@@ -156,22 +138,110 @@ __device__ __forceinline__ void accumulate(const uint32_t (&raw)[NumWords<DT, VE
     for (int j = 0; j < VEC; ++j) acc[j] = acc[j] + v[j];
 }
 
+// One register per task: this lane's sign bits arranged so that a shift and an AND give the XOR
+// mask of any raw dword.  f32: bit j is element j.  bf16 pairs: the even elements' bits sit at
+// 12..15 and the odd elements' at 28..31, so dword j uses (W << (3 - j)) & 0x80008000.
+template <int DT, int VEC>
+__device__ __forceinline__ uint32_t sign_word(uint32_t bits)
+{
+    if constexpr (DT == DT_F32 || VEC == 1) {
+        return bits;
+    } else {
+        uint32_t e = bits & 0x55u, o = (bits >> 1) & 0x55u;
+        e = (e | (e >> 1)) & 0x33u; e = (e | (e >> 2)) & 0x0fu;
+        o = (o | (o >> 1)) & 0x33u; o = (o | (o >> 2)) & 0x0fu;
+        return (e << 12) | (o << 28);
+    }
+}
+
+// acc[j] += (+/-) x[j] with the masks rebuilt from the sign word (keeps registers for loads).
+template <int DT, int VEC>
+__device__ __forceinline__ void accumulate_w(const uint32_t (&raw)[NumWords<DT, VEC>::value], uint32_t W, float (&acc)[VEC])
+{
+    constexpr int NW = NumWords<DT, VEC>::value;
+    uint32_t t[NW];
+    if constexpr (DT == DT_F32) {
+#pragma unroll
+        for (int j = 0; j < NW; ++j) t[j] = raw[j] ^ ((W << (31 - j)) & 0x80000000u);
+    } else if constexpr (VEC == 1) {
+        t[0] = raw[0] ^ ((W & 1u) << 15);
+    } else {
+#pragma unroll
+        for (int j = 0; j < NW; ++j) t[j] = raw[j] ^ ((W << (3 - j)) & 0x80008000u);
+    }
+    float v[VEC];
+    widen<DT, VEC>(t, v);
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) acc[j] = acc[j] + v[j];
+}
+
+// Workgroup barrier that waits for LDS traffic only, so global loads issued before it stay in flight.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Pack VEC binary32 results into the words that go to memory (bf16: RNE, two per word).
+template <int DT, int VEC> struct OutWords {
+    static constexpr int value = (DT == DT_F32) ? VEC : (VEC == 1 ? 1 : VEC / 2);
+};
+
+template <int DT, int VEC>
+__device__ __forceinline__ void pack_out(const float (&v)[VEC], uint32_t (&w)[OutWords<DT, VEC>::value])
+{
+    if constexpr (DT == DT_F32) {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) w[j] = f2u(v[j]);
+    } else if constexpr (VEC == 1) {
+        w[0] = bf16_rne(v[0]);
+    } else {
+#pragma unroll
+        for (int j = 0; j < VEC / 2; ++j) w[j] = bf16_rne(v[2 * j]) | (bf16_rne(v[2 * j + 1]) << 16);
+    }
+}
+
+template <int DT, int VEC>
+__device__ __forceinline__ void store_words(gptr p, const uint32_t (&w)[OutWords<DT, VEC>::value])
+{
+    constexpr int NW = OutWords<DT, VEC>::value;
+    if constexpr (NW == 1) {
+        if constexpr (DT == DT_F32) __builtin_nontemporal_store(w[0], (RANDES_GLOBAL uint32_t *)p);
+        else __builtin_nontemporal_store((uint16_t)w[0], (RANDES_GLOBAL uint16_t *)p);
+    } else if constexpr (NW == 2) {
+        u32x2 q;
+        q.x = w[0]; q.y = w[1];
+        __builtin_nontemporal_store(q, (RANDES_GLOBAL u32x2 *)p);
+    } else {
+#pragma unroll
+        for (int h = 0; h < NW / 4; ++h) {
+            u32x4 q;
+            q.x = w[4 * h]; q.y = w[4 * h + 1]; q.z = w[4 * h + 2]; q.w = w[4 * h + 3];
+            __builtin_nontemporal_store(q, (RANDES_GLOBAL u32x4 *)p + h);
+        }
+    }
+}
+
+// Keeps every store of a burst behind every load of the burst: a wave that first
+// issues all its loads and then all its stores sustains markedly more HBM
+// bandwidth on this chip than one that alternates them.
+__device__ __forceinline__ void load_store_fence() { asm volatile("" ::: "memory"); }
+
 // Where this workgroup works.
 struct Tile {
     LayerDev L;
-    int layer_slot;     // index into the sub-plan's layer array
-    uint32_t col;       // first column of this lane
+    int layer_slot;       // index into the sub-plan's layer array
+    uint32_t col;         // first column of this lane
     uint32_t col_in_tile;
+    uint32_t tile_col0;   // first column of the workgroup's tile
+    uint32_t cw;          // columns of the workgroup's tile
     uint32_t row0, row_end;
-    uint32_t wy, WY;    // this wave's row phase and the row stride between its rows
-    bool active;        // lane has columns inside the layer
+    uint32_t wy, WY;      // this wave's row phase and the row stride between its rows
+    bool active;          // lane has columns inside the layer
 };
 
 template <int VEC>
 __device__ __forceinline__ Tile locate(const StreamArgs &A)
 {
     const uint32_t bid = blockIdx.x;
-    int lo = 0, hi = A.n_layers;
+    // coarse[i] = layer that holds tile i * 1024: narrows the search to a step or two
+    int lo = (int)A.coarse[bid >> 10], hi = (int)A.coarse[(bid >> 10) + 1] + 1;
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
         if (A.tile_begin[mid] <= bid) lo = mid; else hi = mid;
@@ -186,9 +256,10 @@ __device__ __forceinline__ Tile locate(const StreamArgs &A)
     const uint32_t wx = wave & (t.L.wx - 1u);
     t.WY = (uint32_t)WAVES >> t.L.wx_shift;
     t.wy = wave >> t.L.wx_shift;
-    const uint32_t cw = t.L.wx * 64u * VEC;
+    t.cw = t.L.wx * 64u * VEC;
     t.col_in_tile = (wx * 64u + lane) * VEC;
-    t.col = cb * cw + t.col_in_tile;
+    t.tile_col0 = cb * t.cw;
+    t.col = t.tile_col0 + t.col_in_tile;
     t.active = t.col < (uint32_t)t.L.cols;
     t.row0 = rc * t.L.tile_rows;
     const uint32_t re = t.row0 + t.L.tile_rows;
@@ -196,215 +267,229 @@ __device__ __forceinline__ Tile locate(const StreamArgs &A)
     return t;
 }
 
+// The workgroup produces the sign bits of its tile's columns once, cooperatively,
+// into LDS: sbits[(task * nblk + blk) * 4 + word] for the generator blocks that
+// cover [tile_col0, tile_col0 + cw).  A tile may start in the middle of a
+// 128-column block (element-wise kernels), so bits are addressed relative to the
+// block that contains the tile's first column.  Returns nblk.  Caller barriers.
+__device__ __forceinline__ uint32_t stage_sign_bits(uint32_t *sbits, const Tile &t, const uint32_t *keys,
+                                                    uint32_t n_keys, uint32_t key_lo, uint32_t key_hi)
+{
+    const uint32_t lead = t.tile_col0 & 127u;
+    const uint32_t nblk = (lead + t.cw + 127u) / 128u;
+    if (t.L.flip) {
+        for (uint32_t q = threadIdx.x; q < n_keys * nblk; q += WG) {
+            const uint32_t i = q / nblk, blk = q % nblk;
+            const uint32_t klo = keys ? keys[2 * i] : key_lo, khi = keys ? keys[2 * i + 1] : key_hi;
+            const u32x4_t o = sign_block(klo, khi, t.L.layer_id, (t.tile_col0 >> 7) + blk);
+            uint32_t *w = sbits + (size_t)q * 4u;
+            w[0] = o.w[0]; w[1] = o.w[1]; w[2] = o.w[2]; w[3] = o.w[3];
+        }
+    }
+    return nblk;
+}
+
+// This lane's VEC sign bits of task i, out of the staged words.
+template <int VEC>
+__device__ __forceinline__ uint32_t lane_bits_from_lds(const uint32_t *sbits, const Tile &t, uint32_t nblk, uint32_t i)
+{
+    if (!t.L.flip) return 0u;
+    const uint32_t rel = (t.tile_col0 & 127u) + t.col_in_tile;
+    constexpr uint32_t vm = (VEC == 32) ? 0xffffffffu : ((1u << VEC) - 1u);
+    return (sbits[(size_t)i * nblk * 4u + (rel >> 5)] >> (rel & 31u)) & vm;
+}
+
 // ---------------------------------------------------------------------------
 // compress: merged[l] = sum_i D_i^l-flipped delta_i[src_i(l)], binary32, task order.
-// KT > 0: exactly KT tasks, masks hoisted into registers.
-// KT = 0: any number of tasks; the tile's sign bits are produced cooperatively
-//         into LDS once (bits only: the weight stream still bypasses LDS).
+// A wave owns R rows of its column slice per burst.  It first issues the loads of
+// all R rows of all tasks, and while they are in flight the workgroup produces
+// its sign bits; then it accumulates and only then stores the R result rows.
+// KT > 0: exactly KT tasks, every load of the burst in flight at once.
+// KT = 0: any number of tasks, loaded eight at a time for two rows.
 // ---------------------------------------------------------------------------
-template <int DTI, int DTO, int VEC, int KT>
+template <int DTI, int DTO, int VEC, int KT, int R>
 __global__ void __launch_bounds__(WG) merge_kernel(const StreamArgs A)
 {
-    constexpr int NW = NumWords<DTI, VEC>::value;
+    constexpr int NW = NumWords<DTI, VEC>::value, NWO = OutWords<DTO, VEC>::value;
     constexpr uint32_t EBI = (DTI == DT_F32) ? 4 : 2, EBO = (DTO == DT_F32) ? 4 : 2;
+    extern __shared__ uint32_t sbits[];
+    __shared__ gcptr sptr[KT > 0 ? 1 : RANDES_MAX_TASKS];   // KT = 0: tile base pointer of every task
     const Tile t = locate<VEC>(A);
+    const uint32_t K = KT > 0 ? (uint32_t)KT : (uint32_t)A.n_tasks;
     const uint32_t rb_in = (uint32_t)t.L.cols * EBI, rb_out = (uint32_t)t.L.cols * EBO;
     const size_t tile_in = (size_t)t.row0 * rb_in, tile_out = (size_t)t.row0 * rb_out;
     uint32_t off_in = t.wy * rb_in + t.col * EBI;
     uint32_t off_out = t.wy * rb_out + t.col * EBO;
     const uint32_t step_in = t.WY * rb_in, step_out = t.WY * rb_out;
-    char *const dst = (char *)t.L.dst + tile_out;
+    const gptr dst = (gptr)t.L.dst + tile_out;
 
     if constexpr (KT > 0) {
-        if (!t.active) return;
-        const char *src[KT];
-        uint32_t pm[KT][NW];
+        gcptr src[KT];
 #pragma unroll
-        for (int i = 0; i < KT; ++i) {
-            src[i] = (const char *)A.srcs[(size_t)t.layer_slot * KT + i] + tile_in;
-            const uint32_t bits = t.L.flip ? lane_sign_bits<VEC>(A.keys[2 * i], A.keys[2 * i + 1], t.L.layer_id, t.col) : 0u;
-            packed_sign_masks<DTI, VEC>(bits, pm[i]);
-        }
+        for (int i = 0; i < KT; ++i) src[i] = (gcptr)A.srcs[(size_t)t.layer_slot * KT + i] + tile_in;
+        uint32_t raw[R][KT][NW];
         uint32_t r = t.row0 + t.wy;
-        for (; r + t.WY * (MERGE_U - 1) < t.row_end; r += t.WY * MERGE_U) {
-            uint32_t raw[MERGE_U][KT][NW];
+        // first burst's loads go out before the sign bits exist
+        if (t.active) {
 #pragma unroll
-            for (int u = 0; u < MERGE_U; ++u)
+            for (int j = 0; j < R; ++j)
+                if (r + t.WY * j < t.row_end) {
 #pragma unroll
-                for (int i = 0; i < KT; ++i) load_raw<DTI, VEC>(src[i] + off_in + u * step_in, raw[u][i]);
+                    for (int i = 0; i < KT; ++i) load_raw<DTI, VEC>(src[i] + (off_in + j * step_in), raw[j][i]);
+                }
+        }
+        const uint32_t nblk = stage_sign_bits(sbits, t, A.keys, K, 0u, 0u);
+        lds_barrier();
+        if (!t.active) return;
+        uint32_t W[KT];
 #pragma unroll
-            for (int u = 0; u < MERGE_U; ++u) {
+        for (int i = 0; i < KT; ++i) W[i] = sign_word<DTI, VEC>(lane_bits_from_lds<VEC>(sbits, t, nblk, i));
+        // The plan gives a wave at most R rows of a tile, so this one burst is all its work.
+        uint32_t res[R][NWO];
+#pragma unroll
+        for (int j = 0; j < R; ++j)
+            if (r + t.WY * j < t.row_end) {
                 float acc[VEC];
 #pragma unroll
-                for (int j = 0; j < VEC; ++j) acc[j] = 0.0f;
+                for (int q = 0; q < VEC; ++q) acc[q] = 0.0f;
 #pragma unroll
-                for (int i = 0; i < KT; ++i) accumulate<DTI, VEC>(raw[u][i], pm[i], acc);
-                store_vec<DTO, VEC>(dst + off_out + u * step_out, acc);
+                for (int i = 0; i < KT; ++i) accumulate_w<DTI, VEC>(raw[j][i], W[i], acc);
+                pack_out<DTO, VEC>(acc, res[j]);
+                if (!STORE_AT_END) store_words<DTO, VEC>(dst + (off_out + j * step_out), res[j]);
             }
-            off_in += MERGE_U * step_in;
-            off_out += MERGE_U * step_out;
-        }
-        for (; r < t.row_end; r += t.WY) {
-            uint32_t raw[KT][NW];
+        if (STORE_AT_END) {
+            load_store_fence();
 #pragma unroll
-            for (int i = 0; i < KT; ++i) load_raw<DTI, VEC>(src[i] + off_in, raw[i]);
-            float acc[VEC];
-#pragma unroll
-            for (int j = 0; j < VEC; ++j) acc[j] = 0.0f;
-#pragma unroll
-            for (int i = 0; i < KT; ++i) accumulate<DTI, VEC>(raw[i], pm[i], acc);
-            store_vec<DTO, VEC>(dst + off_out, acc);
-            off_in += step_in;
-            off_out += step_out;
+            for (int j = 0; j < R; ++j)
+                if (r + t.WY * j < t.row_end) store_words<DTO, VEC>(dst + (off_out + j * step_out), res[j]);
         }
     } else {
-        extern __shared__ uint32_t sbits[];                 // [n_tasks][words per tile row]
-        __shared__ const char *sptr[RANDES_MAX_TASKS];      // tile base pointer of every task
-        const uint32_t cw = t.L.wx * 64u * VEC;             // columns of the workgroup's tile
-        const uint32_t K = (uint32_t)A.n_tasks;
-        // The tile's first column is a multiple of cw, and cw is a multiple of 64, so a tile may
-        // start in the middle of a 128-column generator block: bits are stored relative to
-        // the block that contains the tile's first column.
-        const uint32_t tile_col0 = t.col - t.col_in_tile;
-        const uint32_t lead = tile_col0 & 127u;             // columns of the first block before the tile
-        const uint32_t nblk = (lead + cw + 127u) / 128u;    // generator blocks per task
-        for (uint32_t q = threadIdx.x; q < K * nblk; q += WG) {
-            const uint32_t i = q / nblk, blk = q % nblk;
-            u32x4_t o;
-            if (t.L.flip) o = sign_block(A.keys[2 * i], A.keys[2 * i + 1], t.L.layer_id, (tile_col0 >> 7) + blk);
-            else { o.w[0] = o.w[1] = o.w[2] = o.w[3] = 0u; }
-            uint32_t *w = sbits + ((size_t)i * nblk + blk) * 4u;
-            w[0] = o.w[0]; w[1] = o.w[1]; w[2] = o.w[2]; w[3] = o.w[3];
-        }
+        const uint32_t nblk = stage_sign_bits(sbits, t, A.keys, K, 0u, 0u);
         for (uint32_t i = threadIdx.x; i < K; i += WG)
-            sptr[i] = (const char *)A.srcs[(size_t)t.layer_slot * K + i] + tile_in;
+            sptr[i] = (gcptr)A.srcs[(size_t)t.layer_slot * K + i] + tile_in;
         __syncthreads();
         if (!t.active) return;
-        const uint32_t rel = lead + t.col_in_tile;          // column relative to the first stored block
-        const uint32_t widx = rel >> 5, sh = rel & 31u;
-        constexpr uint32_t vm = (VEC == 32) ? 0xffffffffu : ((1u << VEC) - 1u);
-        constexpr int KC = 8;
-        uint32_t r = t.row0 + t.wy;
-        for (; r < t.row_end; r += t.WY * MERGE_U) {
-            const bool two = (r + t.WY) < t.row_end;   // MERGE_U == 2 rows per step, second may be missing
-            float acc[MERGE_U][VEC];
+        constexpr int KC = 8;   // tasks loaded per step
+        for (uint32_t r = t.row0 + t.wy; r < t.row_end; r += t.WY * R) {
+            uint32_t res[R][NWO];
 #pragma unroll
-            for (int u = 0; u < MERGE_U; ++u)
+            for (int j0 = 0; j0 < R; j0 += 2) {
+                const bool ok0 = r + t.WY * j0 < t.row_end;
+                const bool ok1 = (j0 + 1 < R) && (r + t.WY * (j0 + 1) < t.row_end);
+                if (ok0) {
+                    float acc[2][VEC];
 #pragma unroll
-                for (int j = 0; j < VEC; ++j) acc[u][j] = 0.0f;
-            for (uint32_t i0 = 0; i0 < K; i0 += KC) {
-                uint32_t raw[MERGE_U][KC][NW];
+                    for (int u = 0; u < 2; ++u)
 #pragma unroll
-                for (int j = 0; j < KC; ++j) {
-                    if (i0 + j < K) {
-                        const char *p = sptr[i0 + j] + off_in;
-                        load_raw<DTI, VEC>(p, raw[0][j]);
-                        if (two) load_raw<DTI, VEC>(p + step_in, raw[1][j]);
+                        for (int q = 0; q < VEC; ++q) acc[u][q] = 0.0f;
+                    for (uint32_t i0 = 0; i0 < K; i0 += KC) {
+                        uint32_t raw[2][KC][NW];
+#pragma unroll
+                        for (int q = 0; q < KC; ++q) {
+                            if (i0 + q < K) {
+                                const gcptr p = sptr[i0 + q] + (off_in + j0 * step_in);
+                                load_raw<DTI, VEC>(p, raw[0][q]);
+                                if (ok1) load_raw<DTI, VEC>(p + step_in, raw[1][q]);
+                            }
+                        }
+#pragma unroll
+                        for (int q = 0; q < KC; ++q) {
+                            if (i0 + q < K) {
+                                const uint32_t W = sign_word<DTI, VEC>(lane_bits_from_lds<VEC>(sbits, t, nblk, i0 + q));
+                                accumulate_w<DTI, VEC>(raw[0][q], W, acc[0]);
+                                if (ok1) accumulate_w<DTI, VEC>(raw[1][q], W, acc[1]);
+                            }
+                        }
                     }
-                }
-#pragma unroll
-                for (int j = 0; j < KC; ++j) {
-                    if (i0 + j < K) {
-                        const uint32_t bits = (sbits[(size_t)(i0 + j) * nblk * 4u + widx] >> sh) & vm;
-                        uint32_t pm[NW];
-                        packed_sign_masks<DTI, VEC>(bits, pm);
-                        accumulate<DTI, VEC>(raw[0][j], pm, acc[0]);
-                        if (two) accumulate<DTI, VEC>(raw[1][j], pm, acc[1]);
-                    }
+                    pack_out<DTO, VEC>(acc[0], res[j0]);
+                    if (j0 + 1 < R) pack_out<DTO, VEC>(acc[1], res[j0 + 1 < R ? j0 + 1 : j0]);
                 }
             }
-            store_vec<DTO, VEC>(dst + off_out, acc[0]);
-            if (two) store_vec<DTO, VEC>(dst + off_out + step_out, acc[1]);
-            off_in += MERGE_U * step_in;
-            off_out += MERGE_U * step_out;
+            load_store_fence();
+#pragma unroll
+            for (int j = 0; j < R; ++j)
+                if (r + t.WY * j < t.row_end) store_words<DTO, VEC>(dst + (off_out + j * step_out), res[j]);
+            off_in += R * step_in;
+            off_out += R * step_out;
         }
     }
 }
 
 // ---------------------------------------------------------------------------
-// retrieve: out[t] = fma(lambda, D-flipped merged[l], base[t]), t = src(l).
+// Two-input bursts shared by retrieve and hot-swap update:
+//   retrieve: out[t] = fma(lambda, D-flipped merged[l], base[t]),  t = src(l)
+//   update:   merged[l] <- merged[l] + (+/-) D-flipped delta[src(l)]
+// X is the stream the sign flip acts on, Y the other input.  Same shape as the
+// merge: loads of R rows, sign bits while they fly, arithmetic, then R stores.
 // ---------------------------------------------------------------------------
+template <int DTX, int DTY, int DTO, int VEC, bool FMA>
+__device__ __forceinline__ void two_input_bursts(const StreamArgs &A, const Tile &t, gcptr px, gcptr py,
+                                                 gptr po, uint32_t *sbits)
+{
+    constexpr uint32_t EBX = (DTX == DT_F32) ? 4 : 2, EBY = (DTY == DT_F32) ? 4 : 2, EBO = (DTO == DT_F32) ? 4 : 2;
+    constexpr int NWX = NumWords<DTX, VEC>::value, NWY = NumWords<DTY, VEC>::value, NWO = OutWords<DTO, VEC>::value;
+    constexpr int R = TWO_INPUT_R;
+    const uint32_t cols = (uint32_t)t.L.cols;
+    px += (size_t)t.row0 * cols * EBX;
+    py += (size_t)t.row0 * cols * EBY;
+    po += (size_t)t.row0 * cols * EBO;
+    uint32_t e = t.wy * cols + t.col;               // element offset inside the tile (times 4 stays below 2^32)
+    const uint32_t estep = t.WY * cols;
+    uint32_t r = t.row0 + t.wy;
+    uint32_t rx[R][NWX], ry[R][NWY];
+    if (t.active) {
+#pragma unroll
+        for (int u = 0; u < R; ++u)
+            if (r + t.WY * u < t.row_end) {
+                load_raw<DTX, VEC>(px + (e + u * estep) * EBX, rx[u]);
+                load_raw<DTY, VEC>(py + (e + u * estep) * EBY, ry[u]);
+            }
+    }
+    const uint32_t nblk = stage_sign_bits(sbits, t, nullptr, 1u, A.key_lo, A.key_hi);
+    lds_barrier();
+    if (!t.active) return;
+    uint32_t bits = lane_bits_from_lds<VEC>(sbits, t, nblk, 0u);
+    if (A.negate) bits = ~bits;
+    const float lambda = A.lambda;
+    // The plan gives a wave at most R rows of a tile, so this one burst is all its work.
+    uint32_t res[R][NWO];
+#pragma unroll
+    for (int u = 0; u < R; ++u)
+        if (r + t.WY * u < t.row_end) {
+            float x[VEC], y[VEC], o[VEC];
+            widen<DTX, VEC>(rx[u], x);
+            widen<DTY, VEC>(ry[u], y);
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                const float xs = u2f(f2u(x[j]) ^ ((bits << (31 - j)) & 0x80000000u));
+                o[j] = FMA ? __builtin_fmaf(lambda, xs, y[j]) : (y[j] + xs);
+            }
+            pack_out<DTO, VEC>(o, res[u]);
+            if (!STORE_AT_END) store_words<DTO, VEC>(po + (e + u * estep) * EBO, res[u]);
+        }
+    if (STORE_AT_END) {
+        load_store_fence();
+#pragma unroll
+        for (int u = 0; u < R; ++u)
+            if (r + t.WY * u < t.row_end) store_words<DTO, VEC>(po + (e + u * estep) * EBO, res[u]);
+    }
+}
+
 template <int DTM, int DTB, int DTO, int VEC>
 __global__ void __launch_bounds__(WG) retrieve_kernel(const StreamArgs A)
 {
-    constexpr uint32_t EBM = (DTM == DT_F32) ? 4 : 2, EBB = (DTB == DT_F32) ? 4 : 2, EBO = (DTO == DT_F32) ? 4 : 2;
+    extern __shared__ uint32_t sbits[];
     const Tile t = locate<VEC>(A);
-    if (!t.active) return;
-    const uint32_t cols = (uint32_t)t.L.cols;
-    const char *pm_ = (const char *)t.L.a + (size_t)t.row0 * cols * EBM;
-    const char *pb_ = (const char *)t.L.b + (size_t)t.row0 * cols * EBB;
-    char *po_ = (char *)t.L.dst + (size_t)t.row0 * cols * EBO;
-    const uint32_t bits = t.L.flip ? lane_sign_bits<VEC>(A.key_lo, A.key_hi, t.L.layer_id, t.col) : 0u;
-    uint32_t sm[VEC];
-#pragma unroll
-    for (int j = 0; j < VEC; ++j) sm[j] = ((bits >> j) & 1u) << 31;
-    const float lambda = A.lambda;
-    uint32_t e = t.wy * cols + t.col;               // element offset inside the tile
-    const uint32_t estep = t.WY * cols;
-    uint32_t r = t.row0 + t.wy;
-    for (; r + t.WY * (RETR_U - 1) < t.row_end; r += t.WY * RETR_U) {
-        uint32_t rm[RETR_U][NumWords<DTM, VEC>::value], rb[RETR_U][NumWords<DTB, VEC>::value];
-#pragma unroll
-        for (int u = 0; u < RETR_U; ++u) {
-            load_raw<DTM, VEC>(pm_ + (size_t)(e + u * estep) * EBM, rm[u]);
-            load_raw<DTB, VEC>(pb_ + (size_t)(e + u * estep) * EBB, rb[u]);
-        }
-#pragma unroll
-        for (int u = 0; u < RETR_U; ++u) {
-            float m[VEC], b[VEC], o[VEC];
-            widen<DTM, VEC>(rm[u], m);
-            widen<DTB, VEC>(rb[u], b);
-#pragma unroll
-            for (int j = 0; j < VEC; ++j) o[j] = __builtin_fmaf(lambda, u2f(f2u(m[j]) ^ sm[j]), b[j]);
-            store_vec<DTO, VEC>(po_ + (size_t)(e + u * estep) * EBO, o);
-        }
-        e += RETR_U * estep;
-    }
-    for (; r < t.row_end; r += t.WY) {
-        uint32_t rm[NumWords<DTM, VEC>::value], rb[NumWords<DTB, VEC>::value];
-        load_raw<DTM, VEC>(pm_ + (size_t)e * EBM, rm);
-        load_raw<DTB, VEC>(pb_ + (size_t)e * EBB, rb);
-        float m[VEC], b[VEC], o[VEC];
-        widen<DTM, VEC>(rm, m);
-        widen<DTB, VEC>(rb, b);
-#pragma unroll
-        for (int j = 0; j < VEC; ++j) o[j] = __builtin_fmaf(lambda, u2f(f2u(m[j]) ^ sm[j]), b[j]);
-        store_vec<DTO, VEC>(po_ + (size_t)e * EBO, o);
-        e += estep;
-    }
+    two_input_bursts<DTM, DTB, DTO, VEC, true>(A, t, (gcptr)t.L.a, (gcptr)t.L.b, (gptr)t.L.dst, sbits);
 }
 
-// ---------------------------------------------------------------------------
-// hot swap: merged[l] <- merged[l] +/- D-flipped delta[src(l)].
-// ---------------------------------------------------------------------------
+// hot swap: the flipped stream is the delta; the other input and the output are merged[l].
 template <int DTM, int DTD, int VEC>
 __global__ void __launch_bounds__(WG) update_kernel(const StreamArgs A)
 {
-    constexpr uint32_t EBM = (DTM == DT_F32) ? 4 : 2, EBD = (DTD == DT_F32) ? 4 : 2;
+    extern __shared__ uint32_t sbits[];
     const Tile t = locate<VEC>(A);
-    if (!t.active) return;
-    const uint32_t cols = (uint32_t)t.L.cols;
-    char *pm_ = (char *)t.L.dst + (size_t)t.row0 * cols * EBM;
-    const char *pd_ = (const char *)t.L.a + (size_t)t.row0 * cols * EBD;
-    uint32_t bits = t.L.flip ? lane_sign_bits<VEC>(A.key_lo, A.key_hi, t.L.layer_id, t.col) : 0u;
-    if (A.negate) bits = ~bits;
-    uint32_t sm[VEC];
-#pragma unroll
-    for (int j = 0; j < VEC; ++j) sm[j] = ((bits >> j) & 1u) << 31;
-    uint32_t e = t.wy * cols + t.col;
-    const uint32_t estep = t.WY * cols;
-    for (uint32_t r = t.row0 + t.wy; r < t.row_end; r += t.WY) {
-        uint32_t rm[NumWords<DTM, VEC>::value], rd[NumWords<DTD, VEC>::value];
-        load_raw<DTM, VEC>(pm_ + (size_t)e * EBM, rm);
-        load_raw<DTD, VEC>(pd_ + (size_t)e * EBD, rd);
-        float m[VEC], d[VEC], o[VEC];
-        widen<DTM, VEC>(rm, m);
-        widen<DTD, VEC>(rd, d);
-#pragma unroll
-        for (int j = 0; j < VEC; ++j) o[j] = m[j] + u2f(f2u(d[j]) ^ sm[j]);
-        store_vec<DTM, VEC>(pm_ + (size_t)e * EBM, o);
-        e += estep;
-    }
+    two_input_bursts<DTD, DTM, DTM, VEC, false>(A, t, (gcptr)t.L.a, (gcptr)t.L.dst, (gptr)t.L.dst, sbits);
 }
 
 // One byte per column: 1 where D is -1.
@@ -451,8 +536,8 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 
     if constexpr (DTAB == DT_BF16) {
-        const uint16_t *Bp = (const uint16_t *)it.B;
-        const uint16_t *Ap = (const uint16_t *)it.A;
+        const RANDES_GLOBAL uint16_t *Bp = (const RANDES_GLOBAL uint16_t *)it.B;
+        const RANDES_GLOBAL uint16_t *Ap = (const RANDES_GLOBAL uint16_t *)it.A;
         for (int32_t k0 = 0; k0 < rank; k0 += 16) {
             uint16_t ab[8], bb[8];
 #pragma unroll
@@ -471,8 +556,8 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc, 0, 0, 0);
         }
     } else {
-        const float *Bp = (const float *)it.B;
-        const float *Ap = (const float *)it.A;
+        const RANDES_GLOBAL float *Bp = (const RANDES_GLOBAL float *)it.B;
+        const RANDES_GLOBAL float *Ap = (const RANDES_GLOBAL float *)it.A;
         for (int32_t k0 = 0; k0 < rank; k0 += 2) {
             const int32_t k = k0 + (int32_t)half;
             const bool k_ok = k < rank;
@@ -488,8 +573,8 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
         const int64_t orow = (int64_t)ty * LORA_TILE_M + 8 * (v / 4) + 4 * (int)half + (v % 4);
         if (orow < it.rows) {
             const float val = scale * acc[v];
-            if constexpr (DTO == DT_F32) ((float *)it.out)[orow * it.cols + col] = val;
-            else ((uint16_t *)it.out)[orow * it.cols + col] = (uint16_t)bf16_rne(val);
+            if constexpr (DTO == DT_F32) ((RANDES_GLOBAL float *)it.out)[orow * it.cols + col] = val;
+            else ((RANDES_GLOBAL uint16_t *)it.out)[orow * it.cols + col] = (uint16_t)bf16_rne(val);
         }
     }
 }
@@ -497,7 +582,16 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
 // ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
+// LDS for the staged sign bits: 16 bytes per (task, 128-column generator block of the widest tile,
+// plus one block for a tile that starts mid-block).
+static size_t sign_bits_lds_bytes(int n_tasks, int vec)
+{
+    return (size_t)n_tasks * (((size_t)WAVES * 64 * vec + 127) / 128 + 1) * 16;
+}
+
 int merge_vec(int dt_in) { return dt_in == DT_BF16 ? 8 : 4; }
+int merge_burst_rows() { return MERGE_R; }
+int two_input_burst_rows() { return TWO_INPUT_R; }
 int retrieve_vec(int dt_merged, int dt_base) { return (dt_merged == DT_BF16 || dt_base == DT_BF16) ? 8 : 4; }
 int update_vec(int dt_merged, int dt_delta) { return (dt_merged == DT_BF16 || dt_delta == DT_BF16) ? 8 : 4; }
 
@@ -506,14 +600,18 @@ static hipError_t merge_dispatch(const StreamArgs &a, hipStream_t s)
 {
     const dim3 grid(a.n_tiles), block(WG);
     // element-wise variant always stages bits in LDS; the vector variant does so above KREG_MAX tasks
-    const int kt = (VEC == 1 || a.n_tasks > KREG_MAX) ? 0 : a.n_tasks;
-    const size_t lds = (size_t)a.n_tasks * (((size_t)WAVES * 64 * VEC + 127) / 128 + 1) * 16;
+    const size_t lds = sign_bits_lds_bytes(a.n_tasks, VEC);
+    if constexpr (VEC == 1) {
+        hipLaunchKernelGGL((merge_kernel<DTI, DTO, VEC, 0, MERGE_R>), grid, block, lds, s, a);
+        return hipGetLastError();
+    }
+    const int kt = a.n_tasks > KREG_MAX ? 0 : a.n_tasks;
     switch (kt) {
-#define RANDES_CASE(K) case K: hipLaunchKernelGGL((merge_kernel<DTI, DTO, VEC, K>), grid, block, 0, s, a); break;
+#define RANDES_CASE(K) case K: hipLaunchKernelGGL((merge_kernel<DTI, DTO, VEC, K, MERGE_R>), grid, block, lds, s, a); break;
     RANDES_CASE(1) RANDES_CASE(2) RANDES_CASE(3) RANDES_CASE(4)
     RANDES_CASE(5) RANDES_CASE(6) RANDES_CASE(7) RANDES_CASE(8)
 #undef RANDES_CASE
-    default: hipLaunchKernelGGL((merge_kernel<DTI, DTO, VEC, 0>), grid, block, lds, s, a); break;
+    default: hipLaunchKernelGGL((merge_kernel<DTI, DTO, VEC, 0, MERGE_R>), grid, block, lds, s, a); break;
     }
     return hipGetLastError();
 }
@@ -537,8 +635,9 @@ template <int DTM, int DTB, int VEC>
 static hipError_t retrieve_dispatch(const StreamArgs &a, int dt_out, hipStream_t s)
 {
     const dim3 grid(a.n_tiles), block(WG);
-    if (dt_out == DT_F32) hipLaunchKernelGGL((retrieve_kernel<DTM, DTB, DT_F32, VEC>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((retrieve_kernel<DTM, DTB, DT_BF16, VEC>), grid, block, 0, s, a);
+    const size_t lds = sign_bits_lds_bytes(1, VEC);
+    if (dt_out == DT_F32) hipLaunchKernelGGL((retrieve_kernel<DTM, DTB, DT_F32, VEC>), grid, block, lds, s, a);
+    else hipLaunchKernelGGL((retrieve_kernel<DTM, DTB, DT_BF16, VEC>), grid, block, lds, s, a);
     return hipGetLastError();
 }
 
@@ -561,7 +660,7 @@ hipError_t launch_retrieve(const StreamArgs &a, int vec, int dt_merged, int dt_b
 template <int DTM, int DTD, int VEC>
 static hipError_t update_dispatch(const StreamArgs &a, hipStream_t s)
 {
-    hipLaunchKernelGGL((update_kernel<DTM, DTD, VEC>), dim3(a.n_tiles), dim3(WG), 0, s, a);
+    hipLaunchKernelGGL((update_kernel<DTM, DTD, VEC>), dim3(a.n_tiles), dim3(WG), sign_bits_lds_bytes(1, VEC), s, a);
     return hipGetLastError();
 }
 

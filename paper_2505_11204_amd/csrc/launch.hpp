@@ -34,6 +34,10 @@ int merge_vec(int dt_in);
 int retrieve_vec(int dt_merged, int dt_base);
 int update_vec(int dt_merged, int dt_delta);
 
+// Rows of a tile one wave handles in its single load burst (the kernels' compile-time R).
+int merge_burst_rows();
+int two_input_burst_rows();
+
 // Workgroup tile of the LoRA kernel.
 constexpr int LORA_TILE_M = 32, LORA_TILE_N = 128;
 

@@ -71,13 +71,13 @@ int build_source_table(const randes_layer *layers, int32_t n_layers, uint64_t se
     return RANDES_OK;
 }
 
-uint64_t plan_layer_geometry(LayerDev *d, int vec, int tile_rows)
+uint64_t plan_layer_geometry(LayerDev *d, int vec, int rows_per_wave, int max_wx_shift)
 {
     const uint64_t cols = (uint64_t)d->cols, rows = (uint64_t)d->rows;
     // waves along the columns: the widest arrangement that wastes the fewest lanes
     uint32_t best_shift = 0;
     uint64_t best_waste = ~0ull;
-    for (int sh = 2; sh >= 0; --sh) {
+    for (int sh = max_wx_shift; sh >= 0; --sh) {
         const uint64_t cw = (uint64_t)(64 * vec) << sh;
         const uint64_t waste = (cols + cw - 1) / cw * cw - cols;
         if (waste < best_waste) { best_waste = waste; best_shift = (uint32_t)sh; }
@@ -90,13 +90,26 @@ uint64_t plan_layer_geometry(LayerDev *d, int vec, int tile_rows)
     const uint64_t row_bytes = cols * 4;
     const uint64_t max_rows = ((uint64_t)1 << 31) / row_bytes;
     if (max_rows < 17) return 0;
-    uint64_t tr = (uint64_t)tile_rows;
+    uint64_t tr = (uint64_t)rows_per_wave << (2 - best_shift);   // 4 waves: 4 / wx of them stacked along the rows
     if (tr > max_rows - 16) tr = max_rows - 16;
     if (tr > rows) tr = rows;
     if (tr < 1) tr = 1;
     d->tile_rows = (uint32_t)tr;
     const uint64_t n_rc = (rows + tr - 1) / tr;
     return n_rc * d->n_cb;
+}
+
+void build_coarse_index(SubPlan *sp)
+{
+    sp->coarse.clear();
+    if (sp->layers.empty()) { sp->coarse.assign(2, 0u); return; }
+    const uint32_t n_chunks = (sp->n_tiles + 1023u) / 1024u;
+    uint32_t layer = 0;
+    for (uint32_t i = 0; i <= n_chunks; ++i) {
+        const uint64_t tile = std::min<uint64_t>((uint64_t)i * 1024u, sp->n_tiles ? sp->n_tiles - 1u : 0u);
+        while (layer + 1 < sp->layers.size() && sp->tile_begin[layer + 1] <= tile) ++layer;
+        sp->coarse.push_back(layer);
+    }
 }
 
 }  // namespace randes

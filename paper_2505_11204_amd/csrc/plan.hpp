@@ -32,6 +32,7 @@ struct StreamArgs {
     const LayerDev *layers;       // n_layers
     const void *const *srcs;      // merge only: [n_layers][n_tasks] source pointers
     const uint32_t *tile_begin;   // n_layers + 1 prefix sums of tiles
+    const uint32_t *coarse;       // coarse[i] = layer that holds tile 1024 * i (one extra entry at the end)
     const uint32_t *keys;         // merge only: [n_tasks][2] = (seed low, seed high)
     int32_t n_layers;
     int32_t n_tasks;
@@ -46,6 +47,7 @@ struct SubPlan {
     std::vector<LayerDev> layers;
     std::vector<const void *> srcs;     // merge
     std::vector<uint32_t> tile_begin;
+    std::vector<uint32_t> coarse;
     uint32_t n_tiles = 0;
 };
 
@@ -65,8 +67,11 @@ int build_source_table(const randes_layer *layers, int32_t n_layers, uint64_t se
 void layer_perm(uint64_t seed, int32_t group, int32_t group_size, int32_t *perm_out);
 
 // Fill the geometry (n_cb, wx, tile_rows) of one descriptor for lanes that own
-// `vec` columns each; returns the layer's tile count, or 0 if the layer is too
-// wide for 32-bit in-tile offsets.
-uint64_t plan_layer_geometry(LayerDev *d, int vec, int tile_rows);
+// `vec` columns each and waves that own `rows_per_wave` rows of a tile; returns
+// the layer's tile count, or 0 if the layer is too wide for 32-bit in-tile offsets.
+uint64_t plan_layer_geometry(LayerDev *d, int vec, int rows_per_wave, int max_wx_shift = 2);
+
+// coarse[i] = layer holding tile 1024 * i, for i = 0 .. ceil(n_tiles / 1024).
+void build_coarse_index(SubPlan *sp);
 
 }  // namespace randes

@@ -20,9 +20,11 @@ TD = {"f32": torch.float32, "bf16": torch.bfloat16}
 @pytest.fixture(autouse=True)
 def _default_tiles():
     rb.set_tile_rows(0, 0)
+    rb.set_tile_cols(0)
     yield
     torch.cuda.synchronize()
     rb.set_tile_rows(0, 0)
+    rb.set_tile_cols(0)
 
 
 def ragged_stack():
@@ -84,14 +86,15 @@ def test_tiny_config():
     ("bf16", "f32", "f32", "bf16"), ("bf16", "bf16", "bf16", "f32")])
 @pytest.mark.parametrize("n_tasks", [1, 3, 8, 9, 20])
 def test_ragged_stack_all_dtypes(d_in, d_merged, d_base, d_out, n_tasks):
-    rb.set_tile_rows(16, 16)
+    rb.set_tile_rows(3, 5)
+    rb.set_tile_cols(2 if n_tasks % 2 else 4)
     seeds = [42 + i for i in range(n_tasks)]
     run_both(ragged_stack(), n_tasks, seeds, d_in, d_merged, d_base, d_out, 0.3, [0, n_tasks - 1])
 
 
 @pytest.mark.parametrize("n_tasks", [2, 4, 5, 6, 7])
 def test_every_register_resident_task_count(n_tasks):
-    rb.set_tile_rows(32, 32)
+    rb.set_tile_cols(1 if n_tasks % 2 else 0)
     seeds = [1000 + 7 * i for i in range(n_tasks)]
     run_both(ragged_stack(), n_tasks, seeds, "bf16", "bf16", "bf16", "bf16", 1.0, [n_tasks // 2])
     run_both(ragged_stack(), n_tasks, seeds, "f32", "f32", "f32", "f32", 1.0, [n_tasks // 2])
@@ -135,8 +138,9 @@ def test_launch_geometry_does_not_change_results():
     gb = to_gpu(base)
     seeds = list(range(42, 50))
     ref_m = ref_o = None
-    for tr in (1, 7, 16, 128, 1000):
+    for tr, tc in ((0, 0), (1, 4), (2, 2), (3, 1), (4, 2), (7, 1), (1000, 4)):
         rb.set_tile_rows(tr, tr)
+        rb.set_tile_cols(tc)
         m = rb.merge(layers, gd, seeds)
         o = rb.retrieve(layers, m, gb, seeds[3], 0.9)
         torch.cuda.synchronize()

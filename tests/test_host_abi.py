@@ -66,10 +66,6 @@ def test_stack_sizes():
     assert len(wl.t5_lora_targets(wl.t5_base())) == 72
 
 
-def _code(fn, *args):
-    return fn(*args)
-
-
 def test_bad_arguments_are_error_codes_not_crashes(lib):
     L = rb._Layer
     one = (L * 1)(L(4, 4, 0, 3))
@@ -109,5 +105,7 @@ def test_bad_arguments_are_error_codes_not_crashes(lib):
     assert lib.randes_update(one, 1, ptr, 0, None, 0, 1, 0, None) == EINVAL
     assert lib.randes_set_tile_rows(-1, 0) == EINVAL
     assert lib.randes_set_tile_rows(0, 0) == 0
+    assert lib.randes_set_tile_cols(3) == EINVAL
+    assert lib.randes_set_tile_cols(0) == 0
     assert lib.randes_strerror(0) == b"ok"
     assert lib.randes_shutdown() == 0
