@@ -51,47 +51,86 @@ def parse():
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 4 GiB device copy (torch.mul(src, 1.0, out=dst)) three times, so that HBM byte "
                          "counters collected over this command can be scaled by a kernel of known traffic")
-    ap.add_argument("--cpu-sample-rows", type=int, default=1024)
+    ap.add_argument("--cpu-sample-elems", type=int, default=1_600_000_000,
+                    help="size of the oracle's sample (elements per model)")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the plain-streaming probe")
     return ap.parse_args()
 
 
-def cpu_baseline(stack, layers, deltas, base, seeds, dtype, n_requests, sample_rows):
-    """The oracle, as it stands, on the first `sample_rows` rows of every layer of
-    the first block (plus nothing else), with all host threads."""
-    import numpy as np  # noqa: F401
+def cpu_baseline(stack, deltas, base, seeds, dtype, n_requests, target_elems):
+    """The oracle, as it stands, on a bounded sample of the same workload: the leading
+    grouped layers of the stack (whole matrices, about `target_elems` elements), copied
+    from the device, merged once and retrieved for a few tasks with all host threads."""
     import oracle
     code = {"f32": 0, "bf16": 1}[dtype]
-    # first block = the first occurrence of every group id; singletons are left out
-    seen, pick = set(), []
+    pick, n_elem = [], 0
     for idx, l in enumerate(stack):
-        if l.group >= 0 and l.group not in seen:
-            seen.add(l.group)
-            pick.append(idx)
-    sub = [(min(stack[i].rows, sample_rows), stack[i].cols, -1, stack[i].flags & wl.FLIP) for i in pick]
-    n_elem = sum(r * c for r, c, _, _ in sub)
+        if l.group < 0:
+            continue
+        pick.append(idx)
+        n_elem += l.rows * l.cols
+        if n_elem >= target_elems:
+            break
+    sub = [(stack[i].rows, stack[i].cols, stack[i].group, stack[i].flags) for i in pick]
     K = len(seeds)
-    host_d = [[wl.to_numpy(deltas[i][p][:sub[q][0]]) for q, p in enumerate(pick)] for i in range(K)]
-    host_b = [wl.to_numpy(base[p][:sub[q][0]]) for q, p in enumerate(pick)]
+    host_d = [[wl.to_numpy(deltas[i][p]) for p in pick] for i in range(K)]
+    host_b = [wl.to_numpy(base[p]) for p in pick]
     threads = oracle.max_threads()
     t0 = time.perf_counter()
     merged = oracle.merge(sub, host_d, seeds, code, code, n_threads=threads)
     t1 = time.perf_counter()
-    oracle.retrieve(sub, merged, host_b, seeds[0], 1.0, code, code, code, n_threads=threads)
+    n_retr = min(4, n_requests)
+    for q in range(n_retr):
+        oracle.retrieve(sub, merged, host_b, seeds[q % K], 1.0, code, code, code, n_threads=threads)
     t2 = time.perf_counter()
     eb = 4 if dtype == "f32" else 2
     bytes_merge = n_elem * (K * eb + eb)
     bytes_retr = n_elem * 3 * eb
-    t_step = (t1 - t0) + n_requests * (t2 - t1)
+    t_merge, t_retr = t1 - t0, (t2 - t1) / n_retr
+    t_step = t_merge + n_requests * t_retr
     return {
         "value": (bytes_merge + n_requests * bytes_retr) / t_step / 1e9,
         "unit": "GB/s",
         "cores": threads,
         "kind": "oracle",
-        "sample": "first %d rows of each of the %d matrices of block 0 (%d elements, K=%d): one merge %.3f s + "
-                  "one retrieve %.3f s, combined as 1 merge + %d retrieves" % (
-                      sample_rows, len(sub), n_elem, K, t1 - t0, t2 - t1, n_requests),
-        "merge_GBs": bytes_merge / (t1 - t0) / 1e9,
-        "retrieve_GBs": bytes_retr / (t2 - t1) / 1e9,
+        "sample": "the first %d grouped matrices of the stack (%d elements, K=%d): one merge %.2f s + %d retrieves "
+                  "%.2f s each; value combines them as 1 merge + %d retrieves" % (
+                      len(sub), n_elem, K, t_merge, n_retr, t_retr, n_requests),
+        "merge_GBs": bytes_merge / t_merge / 1e9,
+        "retrieve_GBs": bytes_retr / t_retr / 1e9,
+    }
+
+
+def ceilings(flats, merged_flat, out_flat):
+    """What a plain streaming kernel with the same launch shape and nothing of the method in it
+    reaches on this machine, on this workload's own buffers (not part of the timed region)."""
+    nb = min(f.numel() * f.element_size() for f in flats + [merged_flat, out_flat]) // 16384 * 16384
+    def cut(t):
+        return t.view(torch.uint8)[:nb]
+    base, deltas = cut(flats[0]), [cut(f) for f in flats[1:]]
+    m, o = cut(merged_flat), cut(out_flat)
+    K = min(8, len(deltas))
+
+    def run(inputs, output, write):
+        ts = []
+        for _ in range(4):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            rb.probe_stream(inputs, output, write)
+            b.record()
+            b.synchronize()
+            ts.append(a.elapsed_time(b))
+        ts = sorted(ts[1:])
+        n_streams = len(inputs) + (1 if write else 0)
+        return n_streams * nb / (ts[len(ts) // 2] * 1e-3) / 1e9
+    # the probe overwrites merged and out; both are rewritten by every timed step
+    return {
+        "unit": "GB/s",
+        "bytes_per_stream": nb,
+        "read_%d_streams" % K: run(deltas[:K], o, False),
+        "add_%d_reads_1_write" % K: run(deltas[:K], m, True),
+        "add_2_reads_1_write": run([m, base], o, True),
+        "copy_1_read_1_write": run([base], o, True),
     }
 
 
@@ -117,11 +156,12 @@ def main():
     scales = wl.task_scales(K, 1234) if scaled else None
     rb.set_tile_rows(args.merge_rows, args.retrieve_rows)
 
+    flats = []
     base, deltas = wl.make_inputs(stack, K, dtype=dtype, device="cuda", data_seed=1234,
-                                  delta_std=delta_std, scales=scales)
+                                  delta_std=delta_std, scales=scales, flats=flats)
     td = wl.torch_dtype(dtype)
-    _, merged = wl.alloc_stack(stack, td, "cuda")
-    _, out = wl.alloc_stack(stack, td, "cuda")
+    merged_flat, merged = wl.alloc_stack(stack, td, "cuda")
+    out_flat, out = wl.alloc_stack(stack, td, "cuda")
     lt = rb.LayerTable(layers)
     t_deltas = rb.PtrTable([t for per in deltas for t in per], lt)
     t_merged, t_base, t_out = rb.PtrTable(merged, lt), rb.PtrTable(base, lt), rb.PtrTable(out, lt)
@@ -153,6 +193,11 @@ def main():
             torch.mul(src, 1.0, out=dst)
         torch.cuda.synchronize()
         del src, dst
+
+    ceil = None
+    if not args.no_ceilings and n_elem * eb >= (1 << 28):
+        ceil = ceilings(flats, merged_flat, out_flat)
+        torch.cuda.synchronize()
 
     for _ in range(args.warmup):
         step()
@@ -203,8 +248,10 @@ def main():
         "roofline_merge": {"kernel": "merge_kernel", "bound": "hbm", "achieved": merge_gbs, "peak": HBM_PEAK_GBS,
                            "unit": "GB/s", "frac": merge_gbs / HBM_PEAK_GBS, "traffic": None},
     }
+    if ceil is not None:
+        result["config"]["plain_streaming_ceilings"] = ceil
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(stack, layers, deltas, base, seeds, dtype, n_req, args.cpu_sample_rows)
+        result["cpu_baseline"] = cpu_baseline(stack, deltas, base, seeds, dtype, n_req, args.cpu_sample_elems)
     print(json.dumps(result))
 
 

@@ -174,6 +174,16 @@ int randes_set_tile_rows(int32_t merge_rows, int32_t retrieve_rows);
  * Results never depend on it. */
 int randes_set_tile_cols(int32_t max_waves_along_columns);
 
+/* Measurement aid, not part of the method: a plain streaming kernel with the same
+ * launch shape as merge / retrieve and nothing else in it.  Reads n_inputs (1..8)
+ * device streams of `bytes` bytes each (16-byte aligned, bytes a multiple of 16384)
+ * and, if write != 0, stores their element-wise 32-bit integer sum to output
+ * (bytes bytes); if write == 0 nothing is stored and output only needs 16 valid
+ * bytes.  Its bandwidth is the machine's practical ceiling for that mix of reads
+ * and writes, reported beside the method's kernels by the benchmark. */
+int randes_probe_stream(const void *const *inputs, int32_t n_inputs, void *output, int64_t bytes, int32_t write,
+                        void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,7 +25,8 @@ LIB_PATH = os.path.join(_HERE, "librandes.so")
 EXPORTS = ["randes_layer_perm", "randes_source_table", "randes_sign_mask", "randes_merge",
            "randes_retrieve", "randes_update", "randes_lora_materialize",
            "randes_lora_materialize_batched", "randes_strerror", "randes_shutdown",
-           "randes_set_tile_rows", "randes_set_tile_cols"]
+           "randes_set_tile_rows", "randes_set_tile_cols",
+           "randes_probe_stream"]
 
 
 class RandesError(RuntimeError):
@@ -68,6 +69,7 @@ def lib():
     L.randes_shutdown.argtypes = []
     L.randes_set_tile_rows.argtypes = [i32, i32]
     L.randes_set_tile_cols.argtypes = [i32]
+    L.randes_probe_stream.argtypes = [vp, i32, vp, i64, i32, vp]
     for name in EXPORTS:
         if name != "randes_strerror":
             getattr(L, name).restype = ctypes.c_int
@@ -279,6 +281,20 @@ def set_tile_rows(merge_rows=0, retrieve_rows=0):
 def set_tile_cols(max_waves_along_columns=0):
     """Second launch-shape knob (4, 2, 1; 0 = default).  Results do not depend on it."""
     _check(lib().randes_set_tile_cols(int(max_waves_along_columns)))
+
+
+def probe_stream(inputs, output, write=True, stream=None):
+    """Plain streaming probe (measurement aid): output = integer sum of the input
+    streams, or loads only when ``write`` is false.  All tensors flat, equal byte size."""
+    it = PtrTable(inputs)
+    nbytes = inputs[0].numel() * inputs[0].element_size()
+    for t in inputs:
+        if t.numel() * t.element_size() != nbytes:
+            raise ValueError("probe streams differ in size")
+    if write and output.numel() * output.element_size() < nbytes:
+        raise ValueError("probe output too small")
+    _check(lib().randes_probe_stream(it.array, len(inputs), ctypes.c_void_p(output.data_ptr()), nbytes,
+                                     1 if write else 0, _stream(stream)))
 
 
 def shutdown():

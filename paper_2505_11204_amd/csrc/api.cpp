@@ -510,6 +510,20 @@ int randes_set_tile_rows(int32_t merge_rows, int32_t retrieve_rows)
     return RANDES_OK;
 }
 
+int randes_probe_stream(const void *const *inputs, int32_t n_inputs, void *output, int64_t bytes, int32_t write,
+                        void *hip_stream)
+{
+    if (!inputs || !output || n_inputs < 1 || n_inputs > 8) return fail(RANDES_EINVAL, "inputs/output NULL or n_inputs outside 1..8");
+    if (bytes < (int64_t)PROBE_CHUNK_BYTES || bytes % (int64_t)PROBE_CHUNK_BYTES) return fail(RANDES_EINVAL, "bytes must be a positive multiple of 16384");
+    if (bytes / (int64_t)PROBE_CHUNK_BYTES >= (int64_t)1 << 31) return fail(RANDES_ENOTSUP, "stream too long for one launch");
+    for (int32_t k = 0; k < n_inputs; ++k)
+        if (!inputs[k] || !aligned16(inputs[k])) return fail(RANDES_EINVAL, "NULL or unaligned input stream");
+    if (!aligned16(output)) return fail(RANDES_EINVAL, "unaligned output");
+    hipError_t e = launch_probe(inputs, n_inputs, output, (uint64_t)bytes, write, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail(e, "probe launch");
+    return RANDES_OK;
+}
+
 int randes_set_tile_cols(int32_t max_waves_along_columns)
 {
     int shift;

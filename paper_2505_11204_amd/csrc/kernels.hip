@@ -580,6 +580,69 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
 }
 
 // ---------------------------------------------------------------------------
+// Bandwidth probe: the same burst shape with nothing of the method in it (no signs, no
+// permutation, no format conversion): out = sum of K input streams as 32-bit integer adds, or no
+// store at all.  It measures what plain streaming reaches on the machine at hand, which is the
+// yardstick the merge (K reads + 1 write) and retrieve (2 reads + 1 write) kernels are held to.
+// ---------------------------------------------------------------------------
+struct ProbeArgs {
+    gcptr in[8];
+    gptr out;
+    uint64_t n_vec;   // 16-byte vectors per stream
+};
+
+template <int K, bool WRITE>
+__global__ void __launch_bounds__(WG) probe_kernel(const ProbeArgs P)
+{
+    constexpr int R = 4;
+    const uint64_t base = ((uint64_t)blockIdx.x * R * WG + threadIdx.x) * 16u;
+    u32x4 v[R][K];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+            v[r][k] = __builtin_nontemporal_load((const RANDES_GLOBAL u32x4 *)(P.in[k] + base + (uint64_t)r * WG * 16u));
+    u32x4 res[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        res[r] = v[r][0];
+#pragma unroll
+        for (int k = 1; k < K; ++k) res[r] += v[r][k];
+    }
+    load_store_fence();
+    if constexpr (WRITE) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            __builtin_nontemporal_store(res[r], (RANDES_GLOBAL u32x4 *)(P.out + base + (uint64_t)r * WG * 16u));
+    } else {
+        u32x4 t = res[0];
+#pragma unroll
+        for (int r = 1; r < R; ++r) t ^= res[r];
+        // never true for the probe's inputs; keeps the loads alive without a store stream
+        if (t.x == 0x9e3779b9u && t.y == 0x7f4a7c15u && t.z == 0xf39cc060u && t.w == 0x5cedc834u)
+            __builtin_nontemporal_store(t, (RANDES_GLOBAL u32x4 *)P.out);
+    }
+}
+
+hipError_t launch_probe(const void *const *inputs, int n_inputs, void *output, uint64_t bytes, int write, hipStream_t s)
+{
+    ProbeArgs P;
+    for (int k = 0; k < 8; ++k) P.in[k] = (gcptr)inputs[k < n_inputs ? k : 0];
+    P.out = (gptr)output;
+    P.n_vec = bytes / 16u;
+    const dim3 grid((uint32_t)(bytes / PROBE_CHUNK_BYTES)), block(WG);
+#define RANDES_PROBE(K) case K: if (write) hipLaunchKernelGGL((probe_kernel<K, true>), grid, block, 0, s, P); \
+                                else hipLaunchKernelGGL((probe_kernel<K, false>), grid, block, 0, s, P); break;
+    switch (n_inputs) {
+    RANDES_PROBE(1) RANDES_PROBE(2) RANDES_PROBE(3) RANDES_PROBE(4)
+    RANDES_PROBE(5) RANDES_PROBE(6) RANDES_PROBE(7) RANDES_PROBE(8)
+    default: return hipErrorInvalidValue;
+    }
+#undef RANDES_PROBE
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
 // LDS for the staged sign bits: 16 bytes per (task, 128-column generator block of the widest tile,

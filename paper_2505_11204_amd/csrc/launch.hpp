@@ -38,6 +38,11 @@ int update_vec(int dt_merged, int dt_delta);
 int merge_burst_rows();
 int two_input_burst_rows();
 
+// Plain streaming probe: out = sum of n_inputs streams (write != 0) or loads only (write == 0).
+// bytes per stream must be a multiple of PROBE_CHUNK_BYTES.
+constexpr uint64_t PROBE_CHUNK_BYTES = 4u * 256u * 16u;
+hipError_t launch_probe(const void *const *inputs, int n_inputs, void *output, uint64_t bytes, int write, hipStream_t s);
+
 // Workgroup tile of the LoRA kernel.
 constexpr int LORA_TILE_M = 32, LORA_TILE_N = 128;
 

@@ -124,13 +124,15 @@ def task_scales(n_tasks, data_seed, low=0.5, high=2.0):
 
 
 def make_inputs(stack, n_tasks, dtype="f32", device="cpu", data_seed=1234,
-                base_std=0.02, delta_std=1e-3, scales=None, with_base=True):
+                base_std=0.02, delta_std=1e-3, scales=None, with_base=True, flats=None):
     """Seeded synthetic base weights and deltas.
 
     Returns ``(base_views, delta_views)`` where ``delta_views[i][l]`` is model
     i's delta for layer l in its original position.  base ~ N(0, base_std^2),
     delta_i ~ N(0, (delta_std * scales[i])^2), i.i.d.; values are rounded to
     ``dtype`` by torch.  The same (device, seed) always gives the same bits.
+    If ``flats`` is a list, the flat backing buffers (base first, then one per
+    model) are appended to it.
     """
     td = torch_dtype(dtype)
     g = torch.Generator(device=device)
@@ -139,11 +141,15 @@ def make_inputs(stack, n_tasks, dtype="f32", device="cpu", data_seed=1234,
     if with_base:
         bflat, base = alloc_stack(stack, td, device)
         fill_normal(bflat, base_std, g)
+        if flats is not None:
+            flats.append(bflat)
     deltas = []
     for i in range(n_tasks):
         dflat, dviews = alloc_stack(stack, td, device)
         fill_normal(dflat, delta_std * (scales[i] if scales else 1.0), g)
         deltas.append(dviews)
+        if flats is not None:
+            flats.append(dflat)
     return base, deltas
 
 
