@@ -156,6 +156,21 @@ int randes_lora_materialize_batched(int32_t n, const void *const *Bs, const void
                                     float scale, randes_dtype ab_dtype,
                                     void *const *outs, randes_dtype out_dtype, void *hip_stream);
 
+/* Fused LoRA compress (Sec. "Parameter Efficient Finetuning (PEFT) Model Compression" + Sec. 4.3 / 4.4):
+ * superpose T adapters without materialising any of them,
+ *   merged[l] = scale * sum_i B_i[src_i(l)] A_i[src_i(l)] D_i^l
+ *             = scale * [B_1 .. B_T] [A_1 D_1; ..; A_T D_T]        (one rank T*r contraction per layer)
+ * on the matrix cores with binary32 accumulation, rounded once to merged_dtype.
+ *   layers   the adapter-carrying matrices only (rows x cols of the dense update), with flags and groups
+ *   Bs, As   host arrays of n_tasks * n_layers device pointers, [i * n_layers + l] = model i's factors of
+ *            layer l (original position); B is rows x rank, A is rank x cols, row-major
+ * Differs from materialise-then-merge only by rounding: no intermediate rounding of each L_i to the
+ * storage dtype, and the matrix cores' own summation order. */
+int randes_lora_merge(const randes_layer *layers, int32_t n_layers,
+                      const void *const *Bs, const void *const *As, int32_t rank,
+                      int32_t n_tasks, const uint64_t *seeds, float scale, randes_dtype ab_dtype,
+                      void *const *merged, randes_dtype merged_dtype, void *hip_stream);
+
 /* Text for an error code; for RANDES_EHIP the text of the last HIP failure seen
  * by the calling thread.  Never NULL; valid until the thread's next failing call. */
 const char *randes_strerror(int code);

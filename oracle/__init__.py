@@ -74,6 +74,10 @@ def lib():
                                   ctypes.c_int32, ctypes.c_double, ctypes.c_int, ctypes.c_void_p,
                                   ctypes.c_void_p]
         L.oracle_lora.restype = None
+        L.oracle_lora_merge.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                        ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_double,
+                                        ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+        L.oracle_lora_merge.restype = ctypes.c_int
         L.oracle_update.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int,
                                     ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_int,
                                     ctypes.c_int]
@@ -224,6 +228,22 @@ def lora(B, A, scale=1.0, ab_dtype=F32):
     mag = np.zeros((rows, cols), dtype=np.float64)
     lib().oracle_lora(B.ctypes.data, A.ctypes.data, rows, cols, rank, float(scale), ab_dtype,
                       out.ctypes.data, mag.ctypes.data)
+    return out, mag
+
+
+def lora_merge(layers, factors, seeds, scale=1.0, ab_dtype=F32):
+    """factors[i][l] = (B, A) numpy arrays of model i, layer l (original position).
+    Returns (values, magnitudes): lists of float64 arrays, one per slot layer."""
+    n_layers, n_tasks = len(layers), len(seeds)
+    Bs = [_check(factors[i][l][0], ab_dtype) for i in range(n_tasks) for l in range(n_layers)]
+    As = [_check(factors[i][l][1], ab_dtype) for i in range(n_tasks) for l in range(n_layers)]
+    rank = Bs[0].shape[1]
+    out = [np.zeros((layers[l][0], layers[l][1]), dtype=np.float64) for l in range(n_layers)]
+    mag = [np.zeros((layers[l][0], layers[l][1]), dtype=np.float64) for l in range(n_layers)]
+    rc = lib().oracle_lora_merge(_layers_struct(layers), n_layers, _ptr_array(Bs), _ptr_array(As), rank, n_tasks,
+                                 _seed_array(seeds), float(scale), ab_dtype, _ptr_array(out), _ptr_array(mag))
+    if rc != 0:
+        raise ValueError("shape mismatch inside a shuffle group")
     return out, mag
 
 

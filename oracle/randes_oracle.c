@@ -322,6 +322,55 @@ void oracle_lora(const void *B, const void *A, int64_t rows, int64_t cols, int32
 }
 
 /* ------------------------------------------------------------------------
+ * Superposition of LoRA adapters without materialising them (same section,
+ * combined with Sec. 4.3 and Sec. 4.4):
+ *     out[l][r][c] = scale * sum_i (-1)^{s(seed_i, l, c)} * sum_t B_i[src_i(l)][r][t] * A_i[src_i(l)][t][c]
+ * in binary64.  Bs / As are indexed [i * n_layers + l] (original positions).
+ * mag[l], if mag is not NULL, receives |scale| * sum_i sum_t |B||A|.
+ * ---------------------------------------------------------------------- */
+int oracle_lora_merge(const oracle_layer *layers, int32_t n_layers,
+                      const void *const *Bs, const void *const *As, int32_t rank,
+                      int32_t n_tasks, const uint64_t *seeds, double scale, int ab_dtype,
+                      double *const *out, double *const *mag)
+{
+    int32_t *src = (int32_t *)malloc(sizeof(int32_t) * (size_t)n_layers * (size_t)n_tasks);
+    if (oracle_source_table(layers, n_layers, seeds, n_tasks, src) != 0) { free(src); return -1; }
+    for (int32_t l = 0; l < n_layers; ++l) {
+        const int64_t m = layers[l].rows, n = layers[l].cols;
+        uint8_t *sign = (uint8_t *)calloc((size_t)n * (size_t)n_tasks, 1);
+        if (layers[l].flags & ORACLE_FLIP)
+            for (int32_t i = 0; i < n_tasks; ++i)
+                oracle_sign_mask(seeds[i], (uint32_t)l, n, sign + (int64_t)i * n);
+#pragma omp parallel for schedule(static)
+        for (int64_t r = 0; r < m; ++r) {
+            for (int64_t c = 0; c < n; ++c) {
+                double total = 0.0, total_mag = 0.0;
+                for (int32_t i = 0; i < n_tasks; ++i) {
+                    const int32_t t_layer = src[(int64_t)i * n_layers + l];
+                    const void *B = Bs[(int64_t)i * n_layers + t_layer];
+                    const void *A = As[(int64_t)i * n_layers + t_layer];
+                    double acc = 0.0, am = 0.0;
+                    for (int32_t t = 0; t < rank; ++t) {
+                        double b = (double)load_elem(B, r * rank + t, ab_dtype);
+                        double a = (double)load_elem(A, (int64_t)t * n + c, ab_dtype);
+                        acc += b * a;
+                        am += fabs(b) * fabs(a);
+                    }
+                    if (sign[(int64_t)i * n + c]) acc = -acc;
+                    total += acc;
+                    total_mag += am;
+                }
+                out[l][r * n + c] = scale * total;
+                if (mag) mag[l][r * n + c] = fabs(scale) * total_mag;
+            }
+        }
+        free(sign);
+    }
+    free(src);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------
  * Hot swap (Sec. "Model Hot Swapping"): add (sign = +1) or remove (sign = -1)
  * one model in place,
  *     Delta_*[l] <- Delta_*[l] + sign * (-1)^{s(seed, l, c)} * Delta_new[src(l)]

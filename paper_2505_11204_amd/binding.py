@@ -24,7 +24,7 @@ LIB_PATH = os.path.join(_HERE, "librandes.so")
 
 EXPORTS = ["randes_layer_perm", "randes_source_table", "randes_sign_mask", "randes_merge",
            "randes_retrieve", "randes_update", "randes_lora_materialize",
-           "randes_lora_materialize_batched", "randes_strerror", "randes_shutdown",
+           "randes_lora_materialize_batched", "randes_lora_merge", "randes_strerror", "randes_shutdown",
            "randes_set_tile_rows", "randes_set_tile_cols",
            "randes_probe_stream"]
 
@@ -64,6 +64,7 @@ def lib():
                                           ctypes.c_int, vp]
     L.randes_lora_materialize_batched.argtypes = [i32, vp, vp, vp, vp, i32, ctypes.c_float, ctypes.c_int,
                                                   vp, ctypes.c_int, vp]
+    L.randes_lora_merge.argtypes = [vp, i32, vp, vp, i32, i32, vp, ctypes.c_float, ctypes.c_int, vp, ctypes.c_int, vp]
     L.randes_strerror.argtypes = [ctypes.c_int]
     L.randes_strerror.restype = ctypes.c_char_p
     L.randes_shutdown.argtypes = []
@@ -249,28 +250,64 @@ def lora_materialize(B, A, scale=1.0, out=None, out_dtype=None, stream=None):
     return out
 
 
+class LoraBatch:
+    """Marshalled arguments of a batched materialisation, built once and reused."""
+
+    def __init__(self, Bs, As, outs=None, out_dtype=None):
+        n = len(Bs)
+        if n != len(As) or n < 1:
+            raise ValueError("need as many A as B matrices, at least one")
+        self.rank = int(Bs[0].shape[1])
+        for B, A in zip(Bs, As):
+            if B.shape[1] != self.rank or A.shape[0] != self.rank or B.dtype != Bs[0].dtype or A.dtype != Bs[0].dtype:
+                raise ValueError("all adapters of a batch share rank and dtype")
+        if outs is None:
+            od = Bs[0].dtype if out_dtype is None else out_dtype
+            outs = [torch.empty((B.shape[0], A.shape[1]), dtype=od, device=B.device) for B, A in zip(Bs, As)]
+        self.n, self.outs = n, outs
+        self.bt, self.at, self.ot = PtrTable(Bs), PtrTable(As), PtrTable(outs)
+        self.rows = (ctypes.c_int64 * n)(*[int(B.shape[0]) for B in Bs])
+        self.cols = (ctypes.c_int64 * n)(*[int(A.shape[1]) for A in As])
+        for q, o in enumerate(outs):
+            if o.numel() != self.rows[q] * self.cols[q]:
+                raise ValueError("output %d has the wrong size" % q)
+
+    def run(self, scale=1.0, stream=None):
+        _check(lib().randes_lora_materialize_batched(self.n, self.bt.array, self.at.array, self.rows, self.cols,
+                                                     self.rank, ctypes.c_float(scale), self.bt.code,
+                                                     self.ot.array, self.ot.code, _stream(stream)))
+        return self.outs
+
+
 def lora_materialize_batched(Bs, As, scale=1.0, outs=None, out_dtype=None, stream=None):
     """Many adapters in one launch; all share rank and dtypes."""
-    n = len(Bs)
-    if n != len(As) or n < 1:
-        raise ValueError("need as many A as B matrices, at least one")
+    return LoraBatch(Bs, As, outs, out_dtype).run(scale, stream)
+
+
+def lora_merge(layers, factors, seeds, scale=1.0, merged=None, merged_dtype=None, stream=None):
+    """Fused LoRA compress: ``factors[i][l] = (B, A)`` of model i, layer l (original
+    position).  Returns the superposed dense layers, written once."""
+    lt = _layer_table(layers)
+    n_tasks = len(factors)
+    if n_tasks != len(seeds) or n_tasks < 1:
+        raise ValueError("%d seeds for %d models" % (len(seeds), n_tasks))
+    Bs = [f[0] for per in factors for f in per]
+    As = [f[1] for per in factors for f in per]
+    if len(Bs) != n_tasks * lt.n:
+        raise ValueError("need one (B, A) pair per model and layer")
     rank = Bs[0].shape[1]
-    for B, A in zip(Bs, As):
-        if B.shape[1] != rank or A.shape[0] != rank or B.dtype != Bs[0].dtype or A.dtype != Bs[0].dtype:
-            raise ValueError("all adapters of a batch share rank and dtype")
-    if outs is None:
-        od = Bs[0].dtype if out_dtype is None else out_dtype
-        outs = [torch.empty((B.shape[0], A.shape[1]), dtype=od, device=B.device) for B, A in zip(Bs, As)]
-    bt, at, ot = PtrTable(Bs), PtrTable(As), PtrTable(outs)
-    rows = (ctypes.c_int64 * n)(*[int(B.shape[0]) for B in Bs])
-    cols = (ctypes.c_int64 * n)(*[int(A.shape[1]) for A in As])
-    for q, o in enumerate(outs):
-        if o.numel() != rows[q] * cols[q]:
-            raise ValueError("output %d has the wrong size" % q)
-    _check(lib().randes_lora_materialize_batched(n, bt.array, at.array, rows, cols, rank,
-                                                 ctypes.c_float(scale), bt.code, ot.array, ot.code,
-                                                 _stream(stream)))
-    return outs
+    for q, (B, A) in enumerate(zip(Bs, As)):
+        rows, cols = lt.layers[q % lt.n][:2]
+        if tuple(B.shape) != (rows, rank) or tuple(A.shape) != (rank, cols) or A.dtype != Bs[0].dtype or B.dtype != Bs[0].dtype:
+            raise ValueError("factor pair %d does not fit layer %d x %d at rank %d" % (q, rows, cols, rank))
+    bt, at = PtrTable(Bs), PtrTable(As)
+    if merged is None:
+        merged = alloc_like_layers(lt, Bs[0].dtype if merged_dtype is None else merged_dtype, Bs[0].device)
+    mt = _ptr_table(merged, lt)
+    sd = (ctypes.c_uint64 * n_tasks)(*[_u64(s) for s in seeds])
+    _check(lib().randes_lora_merge(lt.array, lt.n, bt.array, at.array, rank, n_tasks, sd, ctypes.c_float(scale),
+                                   bt.code, mt.array, mt.code, _stream(stream)))
+    return merged
 
 
 def set_tile_rows(merge_rows=0, retrieve_rows=0):

@@ -11,8 +11,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librandes.so")
-SOURCES = ["kernels.hip", "plan.cpp", "api.cpp"]
-HEADERS = ["launch.hpp", "plan.hpp", "philox.hpp", os.path.join("..", "..", "include", "randes.h")]
+SOURCES = ["kernels.hip", "lora.hip", "plan.cpp", "api.cpp"]
+HEADERS = ["launch.hpp", "plan.hpp", "philox.hpp", "device_util.hpp", os.path.join("..", "..", "include", "randes.h")]
 
 # -ffp-contract=off: the merge is adds only and the retrieve asks for its one fused
 # multiply-add explicitly, so nothing may be contracted behind the source's back.

@@ -420,6 +420,57 @@ int randes_update(const randes_layer *layers, int32_t n_layers,
     return RANDES_OK;
 }
 
+}  // extern "C"
+
+namespace {
+
+// Upload (or find) the item and segment tables of a LoRA launch and enqueue it.
+int run_lora(std::vector<LoraItem> &items, const std::vector<LoraSeg> &segs, int32_t rank, float scale,
+             int ab_dtype, int out_dtype, void *hip_stream)
+{
+    uint64_t tiles = 0;
+    for (LoraItem &it : items) {
+        it.tiles_x = (uint32_t)(((int64_t)it.cols + LORA_TILE_N - 1) / LORA_TILE_N);
+        it.tile_begin = (uint32_t)tiles;
+        tiles += (uint64_t)it.tiles_x * (uint64_t)(((int64_t)it.rows + LORA_TILE_M - 1) / LORA_TILE_M);
+        if (tiles >= ((uint64_t)1 << 31)) return fail(RANDES_ENOTSUP, "too many tiles for one launch");
+    }
+    int dev, rc;
+    if ((rc = current_device(&dev))) return rc;
+    const size_t items_bytes = (sizeof(LoraItem) * items.size() + 255) & ~(size_t)255;
+    const size_t segs_bytes = sizeof(LoraSeg) * segs.size();
+    std::string key;
+    const int32_t head[3] = { 100, (int32_t)items.size(), (int32_t)segs.size() };
+    append(&key, head, sizeof(head));
+    append(&key, items.data(), sizeof(LoraItem) * items.size());
+    append(&key, segs.data(), segs_bytes);
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    CachedPlan *cp = lookup(key, dev);
+    if (!cp) {
+        std::vector<char> host(items_bytes + segs_bytes, 0);
+        memcpy(host.data(), items.data(), sizeof(LoraItem) * items.size());
+        memcpy(host.data() + items_bytes, segs.data(), segs_bytes);
+        CachedPlan fresh;
+        fresh.key = key;
+        fresh.device = dev;
+        hipError_t e = hipMalloc(&fresh.blob, host.size());
+        if (e != hipSuccess) return hip_fail(e, "hipMalloc(lora tables)");
+        e = hipMemcpy(fresh.blob, host.data(), host.size(), hipMemcpyHostToDevice);
+        if (e != hipSuccess) { (void)hipFree(fresh.blob); return hip_fail(e, "hipMemcpy(lora tables)"); }
+        cp = insert_plan(std::move(fresh));
+    }
+    hipError_t e = launch_lora((const LoraItem *)cp->blob, (int32_t)items.size(),
+                               (const LoraSeg *)((const char *)cp->blob + items_bytes), (uint32_t)tiles, rank, scale,
+                               ab_dtype, out_dtype, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail(e, "lora launch");
+    return RANDES_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
 int randes_lora_materialize_batched(int32_t n, const void *const *Bs, const void *const *As,
                                     const int64_t *rows, const int64_t *cols, int32_t rank,
                                     float scale, randes_dtype ab_dtype,
@@ -430,42 +481,68 @@ int randes_lora_materialize_batched(int32_t n, const void *const *Bs, const void
     if (!dtype_ok(ab_dtype) || !dtype_ok(out_dtype)) return fail(RANDES_EINVAL, "unknown dtype");
     if (!std::isfinite(scale)) return fail(RANDES_EINVAL, "scale is not finite");
     std::vector<LoraItem> items((size_t)n);
-    uint64_t tiles = 0;
+    std::vector<LoraSeg> segs((size_t)n);
     for (int32_t q = 0; q < n; ++q) {
         if (!Bs[q] || !As[q] || !outs[q]) return fail(RANDES_EINVAL, "NULL matrix pointer");
         if (rows[q] < 1 || cols[q] < 1) return fail(RANDES_EINVAL, "rows < 1 or cols < 1");
         if (rows[q] >= (int64_t)1 << 31 || cols[q] >= (int64_t)1 << 31) return fail(RANDES_ENOTSUP, "rows or cols >= 2^31");
         LoraItem &it = items[(size_t)q];
-        it.B = Bs[q]; it.A = As[q]; it.out = outs[q];
+        memset(&it, 0, sizeof(it));
+        it.out = outs[q];
         it.rows = (int32_t)rows[q]; it.cols = (int32_t)cols[q];
-        it.tiles_x = (uint32_t)((cols[q] + LORA_TILE_N - 1) / LORA_TILE_N);
-        it.tile_begin = (uint32_t)tiles;
-        tiles += (uint64_t)it.tiles_x * (uint64_t)((rows[q] + LORA_TILE_M - 1) / LORA_TILE_M);
-        if (tiles >= ((uint64_t)1 << 31)) return fail(RANDES_ENOTSUP, "too many tiles for one launch");
+        it.seg_begin = (uint32_t)q; it.n_seg = 1;
+        LoraSeg &sg = segs[(size_t)q];
+        memset(&sg, 0, sizeof(sg));
+        sg.B = Bs[q]; sg.A = As[q];
     }
-    int dev, rc;
-    if ((rc = current_device(&dev))) return rc;
-    std::string key;
-    const int32_t head[2] = { 100, n };
-    append(&key, head, sizeof(head));
-    append(&key, items.data(), sizeof(LoraItem) * items.size());
+    return run_lora(items, segs, rank, scale, ab_dtype, out_dtype, hip_stream);
+}
 
-    std::lock_guard<std::mutex> lock(g_mu);
-    CachedPlan *cp = lookup(key, dev);
-    if (!cp) {
-        CachedPlan fresh;
-        fresh.key = key;
-        fresh.device = dev;
-        hipError_t e = hipMalloc(&fresh.blob, sizeof(LoraItem) * items.size());
-        if (e != hipSuccess) return hip_fail(e, "hipMalloc(lora table)");
-        e = hipMemcpy(fresh.blob, items.data(), sizeof(LoraItem) * items.size(), hipMemcpyHostToDevice);
-        if (e != hipSuccess) { (void)hipFree(fresh.blob); return hip_fail(e, "hipMemcpy(lora table)"); }
-        cp = insert_plan(std::move(fresh));
+int randes_lora_merge(const randes_layer *layers, int32_t n_layers,
+                      const void *const *Bs, const void *const *As, int32_t rank,
+                      int32_t n_tasks, const uint64_t *seeds, float scale, randes_dtype ab_dtype,
+                      void *const *merged, randes_dtype merged_dtype, void *hip_stream)
+{
+    std::string why;
+    int rc = validate_layers(layers, n_layers, &why);
+    if (rc) return fail(rc, why);
+    if (!Bs || !As || !seeds || !merged) return fail(RANDES_EINVAL, "Bs, As, seeds or merged is NULL");
+    if (n_tasks < 1 || rank < 1) return fail(RANDES_EINVAL, "n_tasks < 1 or rank < 1");
+    if (n_tasks > RANDES_MAX_TASKS) return fail(RANDES_ENOTSUP, "n_tasks above RANDES_MAX_TASKS");
+    if (!dtype_ok(ab_dtype) || !dtype_ok(merged_dtype)) return fail(RANDES_EINVAL, "unknown dtype");
+    if (!std::isfinite(scale)) return fail(RANDES_EINVAL, "scale is not finite");
+    for (int64_t q = 0; q < (int64_t)n_tasks * n_layers; ++q)
+        if (!Bs[q] || !As[q]) return fail(RANDES_EINVAL, "NULL factor pointer");
+    for (int32_t l = 0; l < n_layers; ++l)
+        if (!merged[l]) return fail(RANDES_EINVAL, "NULL merged pointer");
+    std::vector<std::vector<int32_t>> src((size_t)n_tasks);
+    for (int32_t i = 0; i < n_tasks; ++i) {
+        rc = build_source_table(layers, n_layers, seeds[i], &src[(size_t)i], &why);
+        if (rc) return fail(rc, why);
     }
-    hipError_t e = launch_lora((const LoraItem *)cp->blob, n, (uint32_t)tiles, rank, scale, ab_dtype, out_dtype,
-                               (hipStream_t)hip_stream);
-    if (e != hipSuccess) return hip_fail(e, "lora launch");
-    return RANDES_OK;
+    std::vector<LoraItem> items((size_t)n_layers);
+    std::vector<LoraSeg> segs;
+    segs.reserve((size_t)n_layers * (size_t)n_tasks);
+    for (int32_t l = 0; l < n_layers; ++l) {
+        LoraItem &it = items[(size_t)l];
+        memset(&it, 0, sizeof(it));
+        it.out = merged[l];
+        it.rows = (int32_t)layers[l].rows; it.cols = (int32_t)layers[l].cols;
+        it.seg_begin = (uint32_t)segs.size(); it.n_seg = (uint32_t)n_tasks;
+        for (int32_t i = 0; i < n_tasks; ++i) {
+            LoraSeg sg;
+            memset(&sg, 0, sizeof(sg));
+            const int32_t t = src[(size_t)i][(size_t)l];
+            sg.B = Bs[(size_t)i * n_layers + t];
+            sg.A = As[(size_t)i * n_layers + t];
+            sg.key_lo = (uint32_t)(seeds[i] & 0xffffffffu);
+            sg.key_hi = (uint32_t)(seeds[i] >> 32);
+            sg.layer_id = (uint32_t)l;
+            sg.flip = (layers[l].flags & RANDES_FLIP) ? 1u : 0u;
+            segs.push_back(sg);
+        }
+    }
+    return run_lora(items, segs, rank, scale, ab_dtype, merged_dtype, hip_stream);
 }
 
 int randes_lora_materialize(const void *B, const void *A, int64_t rows, int64_t cols, int32_t rank,

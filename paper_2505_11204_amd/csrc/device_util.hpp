@@ -1,0 +1,45 @@
+// Small device-side helpers shared by the streaming and the LoRA kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace randes {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// Layer pointers reach the kernels through tables in memory, so the compiler cannot tell that
+// they point to global memory and would fall back to flat addressing; say so explicitly.
+#define RANDES_GLOBAL __attribute__((address_space(1)))
+typedef const RANDES_GLOBAL char *gcptr;   // read-only global bytes
+typedef RANDES_GLOBAL char *gptr;          // writable global bytes
+
+constexpr int WG = 256;          // threads per workgroup
+constexpr int WAVES = WG / 64;
+constexpr int KREG_MAX = 8;      // merge: up to this many tasks keep their masks in registers
+#ifndef RANDES_MERGE_R
+#define RANDES_MERGE_R 4
+#endif
+#ifndef RANDES_TWO_INPUT_R
+#define RANDES_TWO_INPUT_R 8
+#endif
+#ifndef RANDES_STORE_AT_END
+#define RANDES_STORE_AT_END 1
+#endif
+constexpr bool STORE_AT_END = RANDES_STORE_AT_END != 0;   // hold a burst's results until all of them exist
+constexpr int MERGE_R = RANDES_MERGE_R;          // merge: rows a wave loads before it stores (one burst)
+constexpr int TWO_INPUT_R = RANDES_TWO_INPUT_R;  // retrieve / update: the same
+
+__device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }
+__device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
+
+// binary32 -> bf16 bits, round to nearest, ties to even; NaN stays quiet NaN.
+__device__ __forceinline__ uint32_t bf16_rne(float f)
+{
+    const uint32_t u = f2u(f);
+    uint32_t r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    if ((u & 0x7fffffffu) > 0x7f800000u) r = (u >> 16) | 0x40u;
+    return r;
+}
+
+}  // namespace randes

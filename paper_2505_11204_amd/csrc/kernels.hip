@@ -11,47 +11,11 @@
 // folded into the pointer tables.
 #include <hip/hip_runtime.h>
 
+#include "device_util.hpp"
 #include "launch.hpp"
 #include "philox.hpp"
 
 namespace randes {
-
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
-// Layer pointers reach the kernels through tables in memory, so the compiler cannot tell that
-// they point to global memory and would fall back to flat addressing; say so explicitly.
-#define RANDES_GLOBAL __attribute__((address_space(1)))
-typedef const RANDES_GLOBAL char *gcptr;   // read-only global bytes
-typedef RANDES_GLOBAL char *gptr;          // writable global bytes
-
-constexpr int WG = 256;          // threads per workgroup
-constexpr int WAVES = WG / 64;
-constexpr int KREG_MAX = 8;      // merge: up to this many tasks keep their masks in registers
-#ifndef RANDES_MERGE_R
-#define RANDES_MERGE_R 4
-#endif
-#ifndef RANDES_TWO_INPUT_R
-#define RANDES_TWO_INPUT_R 8
-#endif
-#ifndef RANDES_STORE_AT_END
-#define RANDES_STORE_AT_END 1
-#endif
-constexpr bool STORE_AT_END = RANDES_STORE_AT_END != 0;   // hold a burst's results until all of them exist
-constexpr int MERGE_R = RANDES_MERGE_R;          // merge: rows a wave loads before it stores (one burst)
-constexpr int TWO_INPUT_R = RANDES_TWO_INPUT_R;  // retrieve / update: the same
-
-__device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }
-__device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
-
-// binary32 -> bf16 bits, round to nearest, ties to even; NaN stays quiet NaN.
-__device__ __forceinline__ uint32_t bf16_rne(float f)
-{
-    const uint32_t u = f2u(f);
-    uint32_t r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-    if ((u & 0x7fffffffu) > 0x7f800000u) r = (u >> 16) | 0x40u;
-    return r;
-}
 
 template <int DT, int VEC> struct NumWords {
     static constexpr int value = (DT == DT_F32) ? VEC : (VEC == 1 ? 1 : VEC / 2);
@@ -502,84 +466,6 @@ __global__ void __launch_bounds__(WG) sign_mask_kernel(uint32_t key_lo, uint32_t
 }
 
 // ---------------------------------------------------------------------------
-// LoRA delta on the matrix cores: out = scale * B (rows x rank) * A (rank x cols).
-// A workgroup owns 32 rows x 128 columns; each wave owns one 32 x 32 block and
-// runs v_mfma_f32_32x32x16_bf16 (bf16 factors) or v_mfma_f32_32x32x2_f32 over
-// the rank.  Operand layout of the 32x32 MFMAs: lane L supplies row (L % 32) of
-// the left operand and column (L % 32) of the right operand, for the depth
-// slice owned by lane half (L / 32); accumulator register v of lane L is
-// output row 8*(v/4) + 4*(L/32) + (v%4), column L % 32.
-// ---------------------------------------------------------------------------
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-template <int DTAB, int DTO>
-__global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t n_items, int32_t rank, float scale)
-{
-    const uint32_t bid = blockIdx.x;
-    int lo = 0, hi = n_items;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (items[mid].tile_begin <= bid) lo = mid; else hi = mid;
-    }
-    const LoraItem it = items[lo];
-    const uint32_t idx = bid - it.tile_begin;
-    const uint32_t tx = idx % it.tiles_x, ty = idx / it.tiles_x;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t lane = threadIdx.x & 63u;
-    const uint32_t half = lane >> 5, l32 = lane & 31u;
-    const int64_t row = (int64_t)ty * LORA_TILE_M + l32;            // left operand row of this lane
-    const int64_t col = (int64_t)tx * LORA_TILE_N + wave * 32 + l32; // right operand column of this lane
-    const bool row_ok = row < it.rows, col_ok = col < it.cols;
-    f32x16 acc;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-
-    if constexpr (DTAB == DT_BF16) {
-        const RANDES_GLOBAL uint16_t *Bp = (const RANDES_GLOBAL uint16_t *)it.B;
-        const RANDES_GLOBAL uint16_t *Ap = (const RANDES_GLOBAL uint16_t *)it.A;
-        for (int32_t k0 = 0; k0 < rank; k0 += 16) {
-            uint16_t ab[8], bb[8];
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                const int32_t k = k0 + (int32_t)half * 8 + q;
-                const bool k_ok = k < rank;
-                ab[q] = (row_ok && k_ok) ? Bp[row * rank + k] : (uint16_t)0;
-                bb[q] = (col_ok && k_ok) ? Ap[(int64_t)k * it.cols + col] : (uint16_t)0;
-            }
-            bf16x8 av, bv;
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                av[q] = __builtin_bit_cast(__bf16, ab[q]);
-                bv[q] = __builtin_bit_cast(__bf16, bb[q]);
-            }
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc, 0, 0, 0);
-        }
-    } else {
-        const RANDES_GLOBAL float *Bp = (const RANDES_GLOBAL float *)it.B;
-        const RANDES_GLOBAL float *Ap = (const RANDES_GLOBAL float *)it.A;
-        for (int32_t k0 = 0; k0 < rank; k0 += 2) {
-            const int32_t k = k0 + (int32_t)half;
-            const bool k_ok = k < rank;
-            const float a = (row_ok && k_ok) ? Bp[row * rank + k] : 0.0f;
-            const float b = (col_ok && k_ok) ? Ap[(int64_t)k * it.cols + col] : 0.0f;
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
-        }
-    }
-
-    if (!col_ok) return;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int64_t orow = (int64_t)ty * LORA_TILE_M + 8 * (v / 4) + 4 * (int)half + (v % 4);
-        if (orow < it.rows) {
-            const float val = scale * acc[v];
-            if constexpr (DTO == DT_F32) ((RANDES_GLOBAL float *)it.out)[orow * it.cols + col] = val;
-            else ((RANDES_GLOBAL uint16_t *)it.out)[orow * it.cols + col] = (uint16_t)bf16_rne(val);
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------
 // Bandwidth probe: the same burst shape with nothing of the method in it (no signs, no
 // permutation, no format conversion): out = sum of K input streams as 32-bit integer adds, or no
 // store at all.  It measures what plain streaming reaches on the machine at hand, which is the
@@ -748,22 +634,6 @@ hipError_t launch_sign_mask(uint32_t key_lo, uint32_t key_hi, uint32_t layer, in
 {
     const uint32_t blocks = (uint32_t)((cols + WG - 1) / WG);
     hipLaunchKernelGGL(sign_mask_kernel, dim3(blocks), dim3(WG), 0, s, key_lo, key_hi, layer, cols, mask_out);
-    return hipGetLastError();
-}
-
-hipError_t launch_lora(const LoraItem *items_dev, int32_t n_items, uint32_t n_tiles, int32_t rank, float scale,
-                       int dt_ab, int dt_out, hipStream_t s)
-{
-    if (n_tiles == 0) return hipSuccess;
-    const dim3 grid(n_tiles), block(WG);
-    if (dt_ab == DT_BF16 && dt_out == DT_BF16)
-        hipLaunchKernelGGL((lora_kernel<DT_BF16, DT_BF16>), grid, block, 0, s, items_dev, n_items, rank, scale);
-    else if (dt_ab == DT_BF16)
-        hipLaunchKernelGGL((lora_kernel<DT_BF16, DT_F32>), grid, block, 0, s, items_dev, n_items, rank, scale);
-    else if (dt_out == DT_BF16)
-        hipLaunchKernelGGL((lora_kernel<DT_F32, DT_BF16>), grid, block, 0, s, items_dev, n_items, rank, scale);
-    else
-        hipLaunchKernelGGL((lora_kernel<DT_F32, DT_F32>), grid, block, 0, s, items_dev, n_items, rank, scale);
     return hipGetLastError();
 }
 

@@ -16,17 +16,22 @@ hipError_t launch_update(const StreamArgs &a, int vec, int dt_merged, int dt_del
 hipError_t launch_sign_mask(uint32_t key_lo, uint32_t key_hi, uint32_t layer, int64_t cols,
                             uint8_t *mask_out, hipStream_t s);
 
-// One matrix of a LoRA batch.
+// One output matrix of a LoRA launch: out = scale * sum over its segments of B A D.
 struct LoraItem {
-    const void *B;   // rows x rank
-    const void *A;   // rank x cols
-    void *out;       // rows x cols
+    void *out;            // rows x cols
     int32_t rows, cols;
     uint32_t tiles_x;     // workgroup tiles along the columns
     uint32_t tile_begin;  // first workgroup of this matrix
+    uint32_t seg_begin, n_seg;
 };
-hipError_t launch_lora(const LoraItem *items_dev, int32_t n_items, uint32_t n_tiles, int32_t rank, float scale,
-                       int dt_ab, int dt_out, hipStream_t s);
+// One term B A D of an output matrix.
+struct LoraSeg {
+    const void *B;        // rows x rank
+    const void *A;        // rank x cols
+    uint32_t key_lo, key_hi, layer_id, flip;   // the sign diagonal D (flip = 0: identity)
+};
+hipError_t launch_lora(const LoraItem *items_dev, int32_t n_items, const LoraSeg *segs_dev, uint32_t n_tiles,
+                       int32_t rank, float scale, int dt_ab, int dt_out, hipStream_t s);
 
 // Columns per lane of the vector kernels for a call whose widest-count stream
 // holds bf16 (8) or only f32 (4).
@@ -44,6 +49,6 @@ constexpr uint64_t PROBE_CHUNK_BYTES = 4u * 256u * 16u;
 hipError_t launch_probe(const void *const *inputs, int n_inputs, void *output, uint64_t bytes, int write, hipStream_t s);
 
 // Workgroup tile of the LoRA kernel.
-constexpr int LORA_TILE_M = 32, LORA_TILE_N = 128;
+constexpr int LORA_TILE_M = 32, LORA_TILE_N = 512;
 
 }  // namespace randes

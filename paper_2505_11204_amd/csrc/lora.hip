@@ -1,0 +1,245 @@
+// LoRA deltas on the matrix cores (Sec. "Parameter Efficient Finetuning (PEFT) Model Compression":
+// Theta_i = Theta_0 + lambda L_i with L_i = B_i A_i).
+//
+//   out = scale * sum over segments s of  B_s (rows x rank) * A_s (rank x cols) * D_s
+//
+// One segment without a sign flip is the plain materialisation L = scale * B A.  K segments, each
+// with the sign diagonal D of its model, is the superposition of K adapters written once:
+// sum_i (B_i A_i) D_i = [B_1 .. B_K] [A_1 D_1; ..; A_K D_K], a rank K*r contraction.
+//
+// A workgroup (4 waves) owns 32 rows x 512 columns; each wave owns 32 x 128 = four 32x32 MFMA
+// accumulators.  Per 16-deep slice of the rank the workgroup stages A's 16 x 512 slab, sign-flipped,
+// into LDS with 16-byte accesses (row-major, as in memory); a lane then gathers the 8 depth values
+// of its column with 2-byte LDS reads, which are conflict-free because neighbouring lanes read
+// neighbouring columns.  B's rows come straight from global memory (16 bytes per lane).  bf16
+// results go back through LDS so that every lane stores 16 contiguous bytes.  The kernel is bound
+// by the output write.
+//
+// Operand layout of the 32x32 MFMAs: lane L supplies row (L % 32) of the left operand and column
+// (L % 32) of the right operand for the depth slice owned by lane half (L / 32); accumulator
+// register v of lane L is output row 8*(v/4) + 4*(L/32) + (v%4), column L % 32.
+#include <hip/hip_runtime.h>
+
+#include "device_util.hpp"
+#include "launch.hpp"
+#include "philox.hpp"
+
+namespace randes {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int KCH = 16;                 // rank slice per staging step
+constexpr int AS_STRIDE = LORA_TILE_N + 8;   // elements per staged depth row (keeps rows 16-byte aligned)
+constexpr int ST_STRIDE = 136;          // bf16 elements per staged output row (272 B)
+
+template <int DTAB, int DTO>
+__global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t n_items, const LoraSeg *segs,
+                                                  int32_t rank, float scale)
+{
+    constexpr int AT_BYTES = KCH * AS_STRIDE * (DTAB == DT_BF16 ? 2 : 4);
+    constexpr int ST_BYTES = WAVES * LORA_TILE_M * ST_STRIDE * 2;
+    constexpr int SMEM = AT_BYTES > ST_BYTES ? AT_BYTES : ST_BYTES;
+    __shared__ __attribute__((aligned(16))) char smem[SMEM];
+    __shared__ uint32_t sbits[LORA_TILE_N / 32];
+
+    const uint32_t bid = blockIdx.x;
+    int lo = 0, hi = n_items;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (items[mid].tile_begin <= bid) lo = mid; else hi = mid;
+    }
+    const LoraItem it = items[lo];
+    const uint32_t idx = bid - it.tile_begin;
+    const uint32_t tx = idx % it.tiles_x, ty = idx / it.tiles_x;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t lane = tid & 63u, half = lane >> 5, l32 = lane & 31u;
+    const int32_t row0 = (int32_t)ty * LORA_TILE_M, col0 = (int32_t)tx * LORA_TILE_N;
+    const int32_t rows = it.rows, cols = it.cols;
+    const int32_t my_row = row0 + (int32_t)l32;              // left-operand row of this lane
+    const bool row_ok = my_row < rows;
+
+    f32x16 acc[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[b][v] = 0.0f;
+
+    for (uint32_t sg = 0; sg < it.n_seg; ++sg) {
+        const LoraSeg S = segs[it.seg_begin + sg];
+        // sign bits of this tile's 512 columns: four generator blocks (tiles start on multiples of 512)
+        if (tid < LORA_TILE_N / 128) {
+            u32x4_t o;
+            if (S.flip) o = sign_block(S.key_lo, S.key_hi, S.layer_id, ((uint32_t)col0 >> 7) + tid);
+            else { o.w[0] = o.w[1] = o.w[2] = o.w[3] = 0u; }
+            sbits[tid * 4 + 0] = o.w[0]; sbits[tid * 4 + 1] = o.w[1];
+            sbits[tid * 4 + 2] = o.w[2]; sbits[tid * 4 + 3] = o.w[3];
+        }
+        const bool a_vec_ok = (cols % 8 == 0) && (((uintptr_t)S.A & 15u) == 0);
+        const bool b_vec_ok = (rank % 8 == 0) && (((uintptr_t)S.B & 15u) == 0);
+
+        for (int32_t k0 = 0; k0 < rank; k0 += KCH) {
+            __syncthreads();   // the slab of the previous step is consumed; sbits are visible
+            // ---- stage A[k0 .. k0+15][col0 .. col0+511], sign-flipped ----
+            if constexpr (DTAB == DT_BF16) {
+                uint16_t *As = (uint16_t *)smem;
+                const RANDES_GLOBAL uint16_t *Ap = (const RANDES_GLOBAL uint16_t *)S.A;
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    const int32_t kk = (int32_t)(tid >> 6) + 4 * p;      // 0..15 inside the slice
+                    const int32_t k = k0 + kk;
+                    const int32_t c8 = (int32_t)(tid & 63u) * 8;         // column inside the tile
+                    const int32_t c = col0 + c8;
+                    uint32_t w[4] = {0u, 0u, 0u, 0u};
+                    if (k < rank && c < cols) {
+                        if (a_vec_ok) {
+                            const u32x4 q = *(const RANDES_GLOBAL u32x4 *)(Ap + (int64_t)k * cols + c);
+                            w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
+                        } else {
+#pragma unroll
+                            for (int j = 0; j < 8; ++j)
+                                if (c + j < cols) w[j >> 1] |= (uint32_t)Ap[(int64_t)k * cols + c + j] << (16 * (j & 1));
+                        }
+                    }
+                    const uint32_t bits = (sbits[c8 >> 5] >> (c8 & 31)) & 0xffu;
+                    u32x4 q;
+                    q.x = w[0] ^ ((((bits >> 0) & 1u) << 15) | (((bits >> 1) & 1u) << 31));
+                    q.y = w[1] ^ ((((bits >> 2) & 1u) << 15) | (((bits >> 3) & 1u) << 31));
+                    q.z = w[2] ^ ((((bits >> 4) & 1u) << 15) | (((bits >> 5) & 1u) << 31));
+                    q.w = w[3] ^ ((((bits >> 6) & 1u) << 15) | (((bits >> 7) & 1u) << 31));
+                    *(u32x4 *)(As + kk * AS_STRIDE + c8) = q;
+                }
+            } else {
+                uint32_t *As = (uint32_t *)smem;
+                const RANDES_GLOBAL uint32_t *Ap = (const RANDES_GLOBAL uint32_t *)S.A;
+#pragma unroll
+                for (int p = 0; p < 8; ++p) {
+                    const int32_t kk = (int32_t)(tid >> 7) + 2 * p;      // 0..15
+                    const int32_t k = k0 + kk;
+                    const int32_t c4 = (int32_t)(tid & 127u) * 4;
+                    const int32_t c = col0 + c4;
+                    const uint32_t bits = (sbits[c4 >> 5] >> (c4 & 31)) & 0xfu;
+                    u32x4 q = {0u, 0u, 0u, 0u};
+                    if (k < rank) {
+                        if (c < cols) q.x = Ap[(int64_t)k * cols + c];
+                        if (c + 1 < cols) q.y = Ap[(int64_t)k * cols + c + 1];
+                        if (c + 2 < cols) q.z = Ap[(int64_t)k * cols + c + 2];
+                        if (c + 3 < cols) q.w = Ap[(int64_t)k * cols + c + 3];
+                    }
+                    q.x ^= ((bits >> 0) & 1u) << 31; q.y ^= ((bits >> 1) & 1u) << 31;
+                    q.z ^= ((bits >> 2) & 1u) << 31; q.w ^= ((bits >> 3) & 1u) << 31;
+                    *(u32x4 *)(As + kk * AS_STRIDE + c4) = q;
+                }
+            }
+            __syncthreads();
+            // ---- multiply ----
+            if constexpr (DTAB == DT_BF16) {
+                const uint16_t *As = (const uint16_t *)smem;
+                const RANDES_GLOBAL uint16_t *Bp = (const RANDES_GLOBAL uint16_t *)S.B;
+                const int32_t kb = k0 + (int32_t)half * 8;
+                uint32_t aw[4] = {0u, 0u, 0u, 0u};
+                if (row_ok && kb < rank) {
+                    if (b_vec_ok) {
+                        const u32x4 q = *(const RANDES_GLOBAL u32x4 *)(Bp + (int64_t)my_row * rank + kb);
+                        aw[0] = q.x; aw[1] = q.y; aw[2] = q.z; aw[3] = q.w;
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 8; ++j)
+                            if (kb + j < rank) aw[j >> 1] |= (uint32_t)Bp[(int64_t)my_row * rank + kb + j] << (16 * (j & 1));
+                    }
+                }
+                u32x4 aq; aq.x = aw[0]; aq.y = aw[1]; aq.z = aw[2]; aq.w = aw[3];
+                const bf16x8 av = __builtin_bit_cast(bf16x8, aq);
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const uint32_t c = wave * 128u + (uint32_t)b * 32u + l32;
+                    const uint16_t *col = As + (half * 8u) * AS_STRIDE + c;
+                    u32x4 bq;
+                    bq.x = (uint32_t)col[0 * AS_STRIDE] | ((uint32_t)col[1 * AS_STRIDE] << 16);
+                    bq.y = (uint32_t)col[2 * AS_STRIDE] | ((uint32_t)col[3 * AS_STRIDE] << 16);
+                    bq.z = (uint32_t)col[4 * AS_STRIDE] | ((uint32_t)col[5 * AS_STRIDE] << 16);
+                    bq.w = (uint32_t)col[6 * AS_STRIDE] | ((uint32_t)col[7 * AS_STRIDE] << 16);
+                    acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8, bq), acc[b], 0, 0, 0);
+                }
+            } else {
+                const float *As = (const float *)smem;
+                const RANDES_GLOBAL float *Bp = (const RANDES_GLOBAL float *)S.B;
+#pragma unroll
+                for (int st = 0; st < KCH / 2; ++st) {
+                    const int32_t kk = 2 * st + (int32_t)half;
+                    const int32_t k = k0 + kk;
+                    const float a = (row_ok && k < rank) ? Bp[(int64_t)my_row * rank + k] : 0.0f;
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const uint32_t c = wave * 128u + (uint32_t)b * 32u + l32;
+                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, As[kk * AS_STRIDE + c], acc[b], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+
+    // ---- epilogue ----
+    const int32_t wcol0 = col0 + (int32_t)wave * 128;    // first column of this wave's 32 x 128 block
+    if constexpr (DTO == DT_F32) {
+        RANDES_GLOBAL float *out = (RANDES_GLOBAL float *)it.out;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int32_t c = wcol0 + b * 32 + (int32_t)l32;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int32_t r = row0 + 8 * (v / 4) + 4 * (int32_t)half + (v % 4);
+                if (r < rows && c < cols) out[(int64_t)r * cols + c] = scale * acc[b][v];
+            }
+        }
+    } else {
+        __syncthreads();   // everyone is done reading the A slab: reuse the LDS for the output
+        uint16_t *stg = (uint16_t *)smem + wave * (LORA_TILE_M * ST_STRIDE);
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int r = 8 * (v / 4) + 4 * (int)half + (v % 4);
+                stg[r * ST_STRIDE + b * 32 + (int)l32] = (uint16_t)bf16_rne(scale * acc[b][v]);
+            }
+        __syncthreads();
+        RANDES_GLOBAL uint16_t *out = (RANDES_GLOBAL uint16_t *)it.out;
+        const bool o_vec_ok = (cols % 8 == 0) && (((uintptr_t)it.out & 15u) == 0);
+        const int c8 = (int)(lane & 15u) * 8;
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            const int r = p * 4 + (int)(lane >> 4);
+            const int32_t gr = row0 + r, gc = wcol0 + c8;
+            if (gr < rows && gc < cols) {
+                const u32x4 q = *(const u32x4 *)(stg + r * ST_STRIDE + c8);
+                if (o_vec_ok) {
+                    __builtin_nontemporal_store(q, (RANDES_GLOBAL u32x4 *)(out + (int64_t)gr * cols + gc));
+                } else {
+                    const uint32_t w[4] = { q.x, q.y, q.z, q.w };
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (gc + j < cols) out[(int64_t)gr * cols + gc + j] = (uint16_t)(w[j >> 1] >> (16 * (j & 1)));
+                }
+            }
+        }
+    }
+}
+
+hipError_t launch_lora(const LoraItem *items_dev, int32_t n_items, const LoraSeg *segs_dev, uint32_t n_tiles,
+                       int32_t rank, float scale, int dt_ab, int dt_out, hipStream_t s)
+{
+    if (n_tiles == 0) return hipSuccess;
+    const dim3 grid(n_tiles), block(WG);
+    if (dt_ab == DT_BF16 && dt_out == DT_BF16)
+        hipLaunchKernelGGL((lora_kernel<DT_BF16, DT_BF16>), grid, block, 0, s, items_dev, n_items, segs_dev, rank, scale);
+    else if (dt_ab == DT_BF16)
+        hipLaunchKernelGGL((lora_kernel<DT_BF16, DT_F32>), grid, block, 0, s, items_dev, n_items, segs_dev, rank, scale);
+    else if (dt_out == DT_BF16)
+        hipLaunchKernelGGL((lora_kernel<DT_F32, DT_BF16>), grid, block, 0, s, items_dev, n_items, segs_dev, rank, scale);
+    else
+        hipLaunchKernelGGL((lora_kernel<DT_F32, DT_F32>), grid, block, 0, s, items_dev, n_items, segs_dev, rank, scale);
+    return hipGetLastError();
+}
+
+}  // namespace randes

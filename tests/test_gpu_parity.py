@@ -321,3 +321,35 @@ def test_lora_deltas_feed_the_merge_bit_exactly():
     o_m = oracle.merge(layers, [[to_np(t) for t in per] for per in deltas], seeds, 1, 1, n_threads=8)
     for l in range(3):
         compare(m[l], o_m[l], "lora merge %d" % l)
+
+
+@pytest.mark.parametrize("dt_ab,dt_out", [("bf16", "bf16"), ("bf16", "f32"), ("f32", "f32")])
+@pytest.mark.parametrize("rank,n_tasks", [(16, 8), (5, 3), (40, 2)])
+def test_fused_lora_merge(dt_ab, dt_out, rank, n_tasks):
+    # sum_i (B_i A_i) D_i with the shuffle, written once: against the float64 oracle
+    stack = [Layer(70, 520, 0, SRSF), Layer(64, 1032, 1, SRSF), Layer(70, 520, 0, SRSF), Layer(33, 77, -1, FLIP),
+             Layer(64, 1032, 1, SRSF), Layer(70, 520, 0, SRSF)]
+    layers = layers_of(stack)
+    seeds = [42 + i for i in range(n_tasks)]
+    factors = wl.make_lora_factors(stack, list(range(len(stack))), n_tasks, rank=rank, dtype=dt_ab, device="cpu")
+    got = rb.lora_merge(layers, [[(B.cuda(), A.cuda()) for (B, A) in per] for per in factors], seeds, 0.5,
+                        merged_dtype=TD[dt_out])
+    want, mag = oracle.lora_merge(layers, [[(to_np(B), to_np(A)) for (B, A) in per] for per in factors], seeds, 0.5,
+                                  CODE[dt_ab])
+    for l in range(len(stack)):
+        g = got[l].float().cpu().numpy().astype(np.float64)
+        tol = n_tasks * rank * 2.0 ** -24 * mag[l] + 2.0 ** -23 * np.abs(want[l]) + 1e-45
+        if dt_out == "bf16":
+            tol = tol + 2.0 ** -8 * np.abs(want[l]) + 2.0 ** -133
+        err = np.abs(g - want[l])
+        assert (err <= tol).all(), (l, err.max())
+    # and it agrees with materialise-then-merge up to the intermediate bf16 rounding of each L_i
+    if dt_ab == "bf16" and dt_out == "bf16":
+        gf = [[(B.cuda(), A.cuda()) for (B, A) in per] for per in factors]
+        deltas = [[rb.lora_materialize(B, A, 0.5) for (B, A) in per] for per in gf]
+        two_step = rb.merge(layers, deltas, seeds)
+        for l in range(len(stack)):
+            a, b = got[l].float(), two_step[l].float()
+            # each of the n_tasks intermediate roundings is at most half a bf16 ulp of its own L_i
+            bound = n_tasks * 2.0 ** -8 * max(d[l].float().abs().max().item() for d in deltas) + 2.0 ** -7 * b.abs().max().item()
+            assert ((a - b).abs() <= bound).all()

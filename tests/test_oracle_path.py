@@ -318,6 +318,33 @@ def test_lora_matches_float64_matmul_and_special_cases():
                        rtol=1e-14, atol=0)
 
 
+def test_fused_lora_merge_equals_explicit_matrix_products():
+    # sum_i (B_i A_i) D_i with the shuffle: against numpy float64 products, explicit diagonal
+    # matrices and the permutations drawn separately
+    layers = [(6, 9, 0, SRSF)] * 3 + [(4, 5, -1, FLIP)]
+    rng = np.random.default_rng(11)
+    seeds = [7, 8, 9]
+    rank = 3
+    factors = [[(rng.standard_normal((m, rank)).astype(np.float32), rng.standard_normal((rank, n)).astype(np.float32))
+                for (m, n, _, _) in layers] for _ in seeds]
+    got, mag = oracle.lora_merge(layers, factors, seeds, 0.5)
+    for l, (m, n, g, fl) in enumerate(layers):
+        want = np.zeros((m, n))
+        wmag = np.zeros((m, n))
+        for i, s in enumerate(seeds):
+            t = l if g < 0 else int(oracle.layer_perm(s, g, 3)[l])   # group members are layers 0, 1, 2
+            B, A = factors[i][t]
+            D = np.diag(1.0 - 2.0 * oracle.sign_mask(s, l, n).astype(np.float64))
+            want += B.astype(np.float64) @ A.astype(np.float64) @ D
+            wmag += np.abs(B).astype(np.float64) @ np.abs(A).astype(np.float64)
+        assert np.allclose(got[l], 0.5 * want, rtol=1e-13, atol=1e-15)
+        assert np.allclose(mag[l], 0.5 * wmag, rtol=1e-13)
+    # one model, no flags: the plain adapter product
+    one, _ = oracle.lora_merge([(6, 9, -1, 0)], [[factors[0][0]]], [1], 1.0)
+    ref, _ = oracle.lora(factors[0][0][0], factors[0][0][1], 1.0)
+    assert np.array_equal(one[0], ref)
+
+
 def test_threads_do_not_change_the_result():
     layers = [(37, 129, 0, SRSF)] * 3
     rng = np.random.default_rng(10)
