@@ -111,6 +111,17 @@ int randes_merge(const randes_layer *layers, int32_t n_layers,
                  randes_dtype delta_dtype,
                  void *const *merged, randes_dtype merged_dtype, void *hip_stream);
 
+/* compress straight from the fine-tuned weights: the delta Delta_i = Theta_i - Theta_0 (Sec. 3) is
+ * formed on the fly in binary32 (one rounding, never rounded to the storage dtype), so no delta
+ * buffers are needed:
+ *   merged[l][r][c] = sum_i (-1)^{s(seeds[i], l, c)} * (weights[i][src_i(l)][r][c] - base[src_i(l)][r][c])
+ * otherwise exactly as randes_merge.  weights: host array of n_tasks * n_layers device pointers
+ * (model i's layer l at [i * n_layers + l]); base: host array of n_layers device pointers; both of
+ * weight_dtype.  For f32 weights the result equals randes_merge on f32 deltas computed as Theta_i - Theta_0. */
+int randes_merge_weights(const randes_layer *layers, int32_t n_layers,
+                         const void *const *weights, const void *const *base, int32_t n_tasks, const uint64_t *seeds,
+                         randes_dtype weight_dtype, void *const *merged, randes_dtype merged_dtype, void *hip_stream);
+
 /* retrieve (Sec. 4, second display; Sec. 4.4 with D^-1 = D; Sec. 4.3 inverse permutation):
  * slot l of the superposition goes back to layer t = src(l) of the requested model,
  *   out[t][r][c] = fma(lambda, (-1)^{s(seed, l, c)} * merged[l][r][c], base[t][r][c])

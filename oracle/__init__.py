@@ -66,6 +66,10 @@ def lib():
                                    ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_int,
                                    ctypes.c_int]
         L.oracle_merge.restype = ctypes.c_int
+        L.oracle_merge_weights.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                           ctypes.c_int32, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p,
+                                           ctypes.c_int, ctypes.c_int]
+        L.oracle_merge_weights.restype = ctypes.c_int
         L.oracle_retrieve.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int,
                                       ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_float,
                                       ctypes.c_void_p, ctypes.c_int, ctypes.c_int]
@@ -185,6 +189,20 @@ def merge(layers, deltas, seeds, delta_dtype=F32, merged_dtype=F32, n_threads=1)
     out = [np.zeros((layers[l][0], layers[l][1]), dtype=_np_dtype(merged_dtype)) for l in range(n_layers)]
     rc = lib().oracle_merge(_layers_struct(layers), n_layers, _ptr_array(flat), n_tasks,
                             _seed_array(seeds), delta_dtype, _ptr_array(out), merged_dtype, n_threads)
+    if rc != 0:
+        raise ValueError("shape mismatch inside a shuffle group")
+    return out
+
+
+def merge_weights(layers, weights, base, seeds, weight_dtype=F32, merged_dtype=F32, n_threads=1):
+    """weights[i][l], base[l]: numpy arrays (original positions).  Deltas are formed on the fly."""
+    n_layers, n_tasks = len(layers), len(seeds)
+    flat = [_check(weights[i][l], weight_dtype, layers[l][0] * layers[l][1])
+            for i in range(n_tasks) for l in range(n_layers)]
+    b = [_check(base[l], weight_dtype, layers[l][0] * layers[l][1]) for l in range(n_layers)]
+    out = [np.zeros((layers[l][0], layers[l][1]), dtype=_np_dtype(merged_dtype)) for l in range(n_layers)]
+    rc = lib().oracle_merge_weights(_layers_struct(layers), n_layers, _ptr_array(flat), _ptr_array(b), n_tasks,
+                                    _seed_array(seeds), weight_dtype, _ptr_array(out), merged_dtype, n_threads)
     if rc != 0:
         raise ValueError("shape mismatch inside a shuffle group")
     return out

@@ -256,6 +256,49 @@ int oracle_merge(const oracle_layer *layers, int32_t n_layers,
 }
 
 /* ------------------------------------------------------------------------
+ * compress from the fine-tuned weights themselves: the delta of Sec. 3,
+ * Delta_i = Theta_i - Theta_0, is formed element by element in binary32 and
+ * then treated exactly as in oracle_merge.  weights[i * n_layers + l] and
+ * base[l] are in their original positions; both have dtype weight_dtype.
+ * ---------------------------------------------------------------------- */
+int oracle_merge_weights(const oracle_layer *layers, int32_t n_layers,
+                         const void *const *weights, const void *const *base, int32_t n_tasks,
+                         const uint64_t *seeds, int weight_dtype, void *const *merged, int merged_dtype,
+                         int n_threads)
+{
+    int32_t *src = (int32_t *)malloc(sizeof(int32_t) * (size_t)n_layers * (size_t)n_tasks);
+    if (oracle_source_table(layers, n_layers, seeds, n_tasks, src) != 0) { free(src); return -1; }
+#ifdef _OPENMP
+    if (n_threads > 0) omp_set_num_threads(n_threads);
+#endif
+    for (int32_t l = 0; l < n_layers; ++l) {
+        const int64_t m = layers[l].rows, n = layers[l].cols;
+        uint8_t *sign = (uint8_t *)calloc((size_t)n * (size_t)n_tasks, 1);
+        if (layers[l].flags & ORACLE_FLIP)
+            for (int32_t i = 0; i < n_tasks; ++i)
+                oracle_sign_mask(seeds[i], (uint32_t)l, n, sign + (int64_t)i * n);
+#pragma omp parallel for schedule(static)
+        for (int64_t r = 0; r < m; ++r) {
+            for (int64_t c = 0; c < n; ++c) {
+                float acc = 0.0f;
+                for (int32_t i = 0; i < n_tasks; ++i) {
+                    const int32_t t = src[(int64_t)i * n_layers + l];
+                    float theta = load_elem(weights[(int64_t)i * n_layers + t], r * n + c, weight_dtype);
+                    float theta0 = load_elem(base[t], r * n + c, weight_dtype);
+                    float x = theta - theta0;
+                    if (sign[(int64_t)i * n + c]) x = -x;
+                    acc = acc + x;
+                }
+                store_elem(merged[l], r * n + c, merged_dtype, acc);
+            }
+        }
+        free(sign);
+    }
+    free(src);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------
  * retrieve (Sec. 4 eq. for hat Theta_i; Sec. 4.4 with D^{-1} = D; Sec. 4.3
  * "the inverse of the corresponding permutation"): slot l of the
  * superposition goes back to layer t = src(l) of the requested model:

@@ -22,7 +22,7 @@ MAX_TASKS = 128
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "librandes.so")
 
-EXPORTS = ["randes_layer_perm", "randes_source_table", "randes_sign_mask", "randes_merge",
+EXPORTS = ["randes_layer_perm", "randes_source_table", "randes_sign_mask", "randes_merge", "randes_merge_weights",
            "randes_retrieve", "randes_update", "randes_lora_materialize",
            "randes_lora_materialize_batched", "randes_lora_merge", "randes_strerror", "randes_shutdown",
            "randes_set_tile_rows", "randes_set_tile_cols",
@@ -57,6 +57,7 @@ def lib():
     L.randes_source_table.argtypes = [vp, i32, u64, vp]
     L.randes_sign_mask.argtypes = [u64, i32, i64, vp, vp]
     L.randes_merge.argtypes = [vp, i32, vp, i32, vp, ctypes.c_int, vp, ctypes.c_int, vp]
+    L.randes_merge_weights.argtypes = [vp, i32, vp, vp, i32, vp, ctypes.c_int, vp, ctypes.c_int, vp]
     L.randes_retrieve.argtypes = [vp, i32, vp, ctypes.c_int, vp, ctypes.c_int, u64, ctypes.c_float,
                                   vp, ctypes.c_int, vp]
     L.randes_update.argtypes = [vp, i32, vp, ctypes.c_int, vp, ctypes.c_int, u64, i32, vp]
@@ -204,6 +205,29 @@ def merge(layers, deltas, seeds, merged=None, merged_dtype=None, stream=None):
     sd = (ctypes.c_uint64 * max(len(seeds), 1))(*[_u64(s) for s in seeds])
     _check(lib().randes_merge(lt.array, lt.n, deltas.array, n_tasks, sd, deltas.code,
                               mt.array, mt.code, _stream(stream)))
+    return merged
+
+
+def merge_weights(layers, weights, base, seeds, merged=None, merged_dtype=None, stream=None):
+    """compress straight from fine-tuned weights and the base (deltas formed on the fly)."""
+    lt = _layer_table(layers)
+    if not isinstance(weights, PtrTable):
+        flat = [t for per_model in weights for t in per_model]
+        if not flat:
+            raise ValueError("no weights given")
+        weights = PtrTable(flat, lt)
+    bt = _ptr_table(base, lt)
+    if bt.dtype != weights.dtype:
+        raise TypeError("weights and base must share a dtype")
+    n_tasks = len(weights.tensors) // max(lt.n, 1)
+    if n_tasks != len(seeds):
+        raise ValueError("%d seeds for %d models" % (len(seeds), n_tasks))
+    if merged is None:
+        merged = alloc_like_layers(lt, weights.dtype if merged_dtype is None else merged_dtype, weights.tensors[0].device)
+    mt = _ptr_table(merged, lt)
+    sd = (ctypes.c_uint64 * max(len(seeds), 1))(*[_u64(s) for s in seeds])
+    _check(lib().randes_merge_weights(lt.array, lt.n, weights.array, bt.array, n_tasks, sd, weights.code,
+                                      mt.array, mt.code, _stream(stream)))
     return merged
 
 

@@ -193,9 +193,14 @@ int randes_sign_mask(uint64_t seed, int32_t layer, int64_t cols, uint8_t *mask_o
     return RANDES_OK;
 }
 
-int randes_merge(const randes_layer *layers, int32_t n_layers,
-                 const void *const *deltas, int32_t n_tasks, const uint64_t *seeds,
-                 randes_dtype delta_dtype, void *const *merged, randes_dtype merged_dtype, void *hip_stream)
+}  // extern "C"
+
+namespace {
+
+// compress from deltas (base == NULL) or from fine-tuned weights and the base (deltas formed on the fly)
+int merge_impl(const randes_layer *layers, int32_t n_layers,
+               const void *const *deltas, const void *const *base, int32_t n_tasks, const uint64_t *seeds,
+               randes_dtype delta_dtype, void *const *merged, randes_dtype merged_dtype, void *hip_stream)
 {
     std::string why;
     int rc = validate_layers(layers, n_layers, &why);
@@ -207,18 +212,19 @@ int randes_merge(const randes_layer *layers, int32_t n_layers,
     for (int64_t q = 0; q < (int64_t)n_tasks * n_layers; ++q)
         if (!deltas[q]) return fail(RANDES_EINVAL, "NULL delta pointer");
     for (int32_t l = 0; l < n_layers; ++l)
-        if (!merged[l]) return fail(RANDES_EINVAL, "NULL merged pointer");
+        if (!merged[l] || (base && !base[l])) return fail(RANDES_EINVAL, "NULL merged or base pointer");
 
     int dev;
     if ((rc = current_device(&dev))) return rc;
     const int32_t tile_rows = g_merge_rows * 4 + g_max_wx_shift;   // both knobs, for the cache key
     std::string key;
-    const int32_t head[6] = { PLAN_MERGE, n_layers, n_tasks, (int32_t)delta_dtype, (int32_t)merged_dtype, tile_rows };
+    const int32_t head[6] = { base ? PLAN_MERGE_WEIGHTS : PLAN_MERGE, n_layers, n_tasks, (int32_t)delta_dtype, (int32_t)merged_dtype, tile_rows };
     append(&key, head, sizeof(head));
     append(&key, layers, sizeof(randes_layer) * (size_t)n_layers);
     append(&key, deltas, sizeof(void *) * (size_t)n_tasks * (size_t)n_layers);
     append(&key, seeds, sizeof(uint64_t) * (size_t)n_tasks);
     append(&key, merged, sizeof(void *) * (size_t)n_layers);
+    if (base) append(&key, base, sizeof(void *) * (size_t)n_layers);
 
     std::lock_guard<std::mutex> lock(g_mu);
     CachedPlan *cp = lookup(key, dev);
@@ -232,8 +238,9 @@ int randes_merge(const randes_layer *layers, int32_t n_layers,
                 const void *p = deltas[(size_t)i * n_layers + l];
                 spans.push_back({ (uintptr_t)p, (uintptr_t)p + n * elem_bytes(delta_dtype), 1 });
             }
+            if (base) spans.push_back({ (uintptr_t)base[l], (uintptr_t)base[l] + n * elem_bytes(delta_dtype), 1 });
         }
-        if (overlap(spans)) return fail(RANDES_EINVAL, "merged overlaps a delta");
+        if (overlap(spans)) return fail(RANDES_EINVAL, "merged overlaps an input");
 
         HostPlan hp;
         std::vector<std::vector<int32_t>> src((size_t)n_tasks);
@@ -244,7 +251,8 @@ int randes_merge(const randes_layer *layers, int32_t n_layers,
             hp.keys.push_back((uint32_t)(seeds[i] >> 32));
         }
         const int vec = merge_vec(delta_dtype);
-        std::vector<const void *> ptrs((size_t)n_tasks);
+        const int n_streams = base ? 2 * n_tasks : n_tasks;
+        std::vector<const void *> ptrs((size_t)n_streams);
         for (int32_t l = 0; l < n_layers; ++l) {
             LayerDev d{};
             d.dst = merged[l];
@@ -256,8 +264,13 @@ int randes_merge(const randes_layer *layers, int32_t n_layers,
             for (int32_t i = 0; i < n_tasks; ++i) {
                 ptrs[(size_t)i] = deltas[(size_t)i * n_layers + src[(size_t)i][(size_t)l]];
                 vector_ok = vector_ok && aligned16(ptrs[(size_t)i]);
+                if (base) {
+                    ptrs[(size_t)(n_tasks + i)] = base[src[(size_t)i][(size_t)l]];
+                    vector_ok = vector_ok && aligned16(ptrs[(size_t)(n_tasks + i)]);
+                }
             }
-            if ((rc = place(&hp, d, ptrs.data(), n_tasks, vector_ok, vec, clamp_rows(g_merge_rows, merge_burst_rows())))) return rc;
+            const int burst = base ? merge_weights_burst_rows() : merge_burst_rows();
+            if ((rc = place(&hp, d, ptrs.data(), n_streams, vector_ok, vec, clamp_rows(g_merge_rows, burst)))) return rc;
         }
         CachedPlan fresh;
         fresh.key = key;
@@ -266,12 +279,35 @@ int randes_merge(const randes_layer *layers, int32_t n_layers,
         cp = insert_plan(std::move(fresh));
     }
     hipStream_t s = (hipStream_t)hip_stream;
-    hipError_t e = launch_merge(cp->vec, 1, delta_dtype, merged_dtype, s);
+    hipError_t e = base ? launch_merge_weights(cp->vec, 1, delta_dtype, merged_dtype, s)
+                        : launch_merge(cp->vec, 1, delta_dtype, merged_dtype, s);
     if (e != hipSuccess) return hip_fail(e, "merge launch");
-    e = launch_merge(cp->scl, 0, delta_dtype, merged_dtype, s);
+    e = base ? launch_merge_weights(cp->scl, 0, delta_dtype, merged_dtype, s)
+             : launch_merge(cp->scl, 0, delta_dtype, merged_dtype, s);
     if (e != hipSuccess) return hip_fail(e, "merge launch (element-wise)");
     return RANDES_OK;
 }
+
+}  // namespace
+
+extern "C" {
+
+int randes_merge(const randes_layer *layers, int32_t n_layers,
+                 const void *const *deltas, int32_t n_tasks, const uint64_t *seeds,
+                 randes_dtype delta_dtype, void *const *merged, randes_dtype merged_dtype, void *hip_stream)
+{
+    return merge_impl(layers, n_layers, deltas, nullptr, n_tasks, seeds, delta_dtype, merged, merged_dtype, hip_stream);
+}
+
+int randes_merge_weights(const randes_layer *layers, int32_t n_layers,
+                         const void *const *weights, const void *const *base, int32_t n_tasks, const uint64_t *seeds,
+                         randes_dtype weight_dtype, void *const *merged, randes_dtype merged_dtype, void *hip_stream)
+{
+    if (!base) return fail(RANDES_EINVAL, "base is NULL");
+    return merge_impl(layers, n_layers, weights, base, n_tasks, seeds, weight_dtype, merged, merged_dtype, hip_stream);
+}
+
+
 
 int randes_retrieve(const randes_layer *layers, int32_t n_layers,
                     const void *const *merged, randes_dtype merged_dtype,

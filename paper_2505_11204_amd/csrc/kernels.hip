@@ -139,6 +139,23 @@ __device__ __forceinline__ void accumulate_w(const uint32_t (&raw)[NumWords<DT, 
     for (int j = 0; j < VEC; ++j) acc[j] = acc[j] + v[j];
 }
 
+// acc[j] += (+/-) (theta[j] - base[j]): the delta Delta_i = Theta_i - Theta_0 (Sec. 3) formed in
+// binary32 on the fly, one rounding, then flipped and added like a stored delta.
+template <int DT, int VEC>
+__device__ __forceinline__ void accumulate_sub(const uint32_t (&rt)[NumWords<DT, VEC>::value],
+                                               const uint32_t (&rb)[NumWords<DT, VEC>::value], uint32_t bits,
+                                               float (&acc)[VEC])
+{
+    float th[VEC], ba[VEC];
+    widen<DT, VEC>(rt, th);
+    widen<DT, VEC>(rb, ba);
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+        const float d = th[j] - ba[j];
+        acc[j] = acc[j] + u2f(f2u(d) ^ ((bits << (31 - j)) & 0x80000000u));
+    }
+}
+
 // Workgroup barrier that waits for LDS traffic only, so global loads issued before it stay in flight.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
@@ -271,13 +288,16 @@ __device__ __forceinline__ uint32_t lane_bits_from_lds(const uint32_t *sbits, co
 // KT > 0: exactly KT tasks, every load of the burst in flight at once.
 // KT = 0: any number of tasks, loaded eight at a time for two rows.
 // ---------------------------------------------------------------------------
-template <int DTI, int DTO, int VEC, int KT, int R>
+// SUB: the inputs are weights, not deltas: task i contributes Theta_i[src] - Theta_0[src]; the
+// source table then holds, per slot layer, the T fine-tuned pointers followed by the T base pointers.
+template <int DTI, int DTO, int VEC, int KT, int R, bool SUB>
 __global__ void __launch_bounds__(WG) merge_kernel(const StreamArgs A)
 {
     constexpr int NW = NumWords<DTI, VEC>::value, NWO = OutWords<DTO, VEC>::value;
     constexpr uint32_t EBI = (DTI == DT_F32) ? 4 : 2, EBO = (DTO == DT_F32) ? 4 : 2;
+    constexpr int NS = SUB ? 2 : 1;                          // input streams per task
     extern __shared__ uint32_t sbits[];
-    __shared__ gcptr sptr[KT > 0 ? 1 : RANDES_MAX_TASKS];   // KT = 0: tile base pointer of every task
+    __shared__ gcptr sptr[KT > 0 ? 1 : NS * RANDES_MAX_TASKS];   // KT = 0: tile base pointer of every stream
     const Tile t = locate<VEC>(A);
     const uint32_t K = KT > 0 ? (uint32_t)KT : (uint32_t)A.n_tasks;
     const uint32_t rb_in = (uint32_t)t.L.cols * EBI, rb_out = (uint32_t)t.L.cols * EBO;
@@ -288,10 +308,10 @@ __global__ void __launch_bounds__(WG) merge_kernel(const StreamArgs A)
     const gptr dst = (gptr)t.L.dst + tile_out;
 
     if constexpr (KT > 0) {
-        gcptr src[KT];
+        gcptr src[NS * KT];
 #pragma unroll
-        for (int i = 0; i < KT; ++i) src[i] = (gcptr)A.srcs[(size_t)t.layer_slot * KT + i] + tile_in;
-        uint32_t raw[R][KT][NW];
+        for (int i = 0; i < NS * KT; ++i) src[i] = (gcptr)A.srcs[(size_t)t.layer_slot * (NS * KT) + i] + tile_in;
+        uint32_t raw[R][NS * KT][NW];
         uint32_t r = t.row0 + t.wy;
         // first burst's loads go out before the sign bits exist
         if (t.active) {
@@ -299,7 +319,7 @@ __global__ void __launch_bounds__(WG) merge_kernel(const StreamArgs A)
             for (int j = 0; j < R; ++j)
                 if (r + t.WY * j < t.row_end) {
 #pragma unroll
-                    for (int i = 0; i < KT; ++i) load_raw<DTI, VEC>(src[i] + (off_in + j * step_in), raw[j][i]);
+                    for (int i = 0; i < NS * KT; ++i) load_raw<DTI, VEC>(src[i] + (off_in + j * step_in), raw[j][i]);
                 }
         }
         const uint32_t nblk = stage_sign_bits(sbits, t, A.keys, K, 0u, 0u);
@@ -307,7 +327,10 @@ __global__ void __launch_bounds__(WG) merge_kernel(const StreamArgs A)
         if (!t.active) return;
         uint32_t W[KT];
 #pragma unroll
-        for (int i = 0; i < KT; ++i) W[i] = sign_word<DTI, VEC>(lane_bits_from_lds<VEC>(sbits, t, nblk, i));
+        for (int i = 0; i < KT; ++i) {
+            const uint32_t bits = lane_bits_from_lds<VEC>(sbits, t, nblk, i);
+            W[i] = SUB ? bits : sign_word<DTI, VEC>(bits);
+        }
         // The plan gives a wave at most R rows of a tile, so this one burst is all its work.
         uint32_t res[R][NWO];
 #pragma unroll
@@ -317,7 +340,10 @@ __global__ void __launch_bounds__(WG) merge_kernel(const StreamArgs A)
 #pragma unroll
                 for (int q = 0; q < VEC; ++q) acc[q] = 0.0f;
 #pragma unroll
-                for (int i = 0; i < KT; ++i) accumulate_w<DTI, VEC>(raw[j][i], W[i], acc);
+                for (int i = 0; i < KT; ++i) {
+                    if constexpr (SUB) accumulate_sub<DTI, VEC>(raw[j][i], raw[j][KT + i], W[i], acc);
+                    else accumulate_w<DTI, VEC>(raw[j][i], W[i], acc);
+                }
                 pack_out<DTO, VEC>(acc, res[j]);
                 if (!STORE_AT_END) store_words<DTO, VEC>(dst + (off_out + j * step_out), res[j]);
             }
@@ -329,11 +355,11 @@ __global__ void __launch_bounds__(WG) merge_kernel(const StreamArgs A)
         }
     } else {
         const uint32_t nblk = stage_sign_bits(sbits, t, A.keys, K, 0u, 0u);
-        for (uint32_t i = threadIdx.x; i < K; i += WG)
-            sptr[i] = (gcptr)A.srcs[(size_t)t.layer_slot * K + i] + tile_in;
+        for (uint32_t i = threadIdx.x; i < NS * K; i += WG)
+            sptr[i] = (gcptr)A.srcs[(size_t)t.layer_slot * (NS * K) + i] + tile_in;
         __syncthreads();
         if (!t.active) return;
-        constexpr int KC = 8;   // tasks loaded per step
+        constexpr int KC = SUB ? 4 : 8;   // tasks loaded per step
         for (uint32_t r = t.row0 + t.wy; r < t.row_end; r += t.WY * R) {
             uint32_t res[R][NWO];
 #pragma unroll
@@ -347,21 +373,30 @@ __global__ void __launch_bounds__(WG) merge_kernel(const StreamArgs A)
 #pragma unroll
                         for (int q = 0; q < VEC; ++q) acc[u][q] = 0.0f;
                     for (uint32_t i0 = 0; i0 < K; i0 += KC) {
-                        uint32_t raw[2][KC][NW];
+                        uint32_t raw[2][NS * KC][NW];
 #pragma unroll
                         for (int q = 0; q < KC; ++q) {
                             if (i0 + q < K) {
-                                const gcptr p = sptr[i0 + q] + (off_in + j0 * step_in);
-                                load_raw<DTI, VEC>(p, raw[0][q]);
-                                if (ok1) load_raw<DTI, VEC>(p + step_in, raw[1][q]);
+#pragma unroll
+                                for (int st = 0; st < NS; ++st) {
+                                    const gcptr p = sptr[st * K + i0 + q] + (off_in + j0 * step_in);
+                                    load_raw<DTI, VEC>(p, raw[0][st * KC + q]);
+                                    if (ok1) load_raw<DTI, VEC>(p + step_in, raw[1][st * KC + q]);
+                                }
                             }
                         }
 #pragma unroll
                         for (int q = 0; q < KC; ++q) {
                             if (i0 + q < K) {
-                                const uint32_t W = sign_word<DTI, VEC>(lane_bits_from_lds<VEC>(sbits, t, nblk, i0 + q));
-                                accumulate_w<DTI, VEC>(raw[0][q], W, acc[0]);
-                                if (ok1) accumulate_w<DTI, VEC>(raw[1][q], W, acc[1]);
+                                const uint32_t bits = lane_bits_from_lds<VEC>(sbits, t, nblk, i0 + q);
+                                if constexpr (SUB) {
+                                    accumulate_sub<DTI, VEC>(raw[0][q], raw[0][KC + q], bits, acc[0]);
+                                    if (ok1) accumulate_sub<DTI, VEC>(raw[1][q], raw[1][KC + q], bits, acc[1]);
+                                } else {
+                                    const uint32_t W = sign_word<DTI, VEC>(bits);
+                                    accumulate_w<DTI, VEC>(raw[0][q], W, acc[0]);
+                                    if (ok1) accumulate_w<DTI, VEC>(raw[1][q], W, acc[1]);
+                                }
                             }
                         }
                     }
@@ -540,6 +575,7 @@ static size_t sign_bits_lds_bytes(int n_tasks, int vec)
 
 int merge_vec(int dt_in) { return dt_in == DT_BF16 ? 8 : 4; }
 int merge_burst_rows() { return MERGE_R; }
+int merge_weights_burst_rows() { return MERGE_WEIGHTS_R; }
 int two_input_burst_rows() { return TWO_INPUT_R; }
 int retrieve_vec(int dt_merged, int dt_base) { return (dt_merged == DT_BF16 || dt_base == DT_BF16) ? 8 : 4; }
 int update_vec(int dt_merged, int dt_delta) { return (dt_merged == DT_BF16 || dt_delta == DT_BF16) ? 8 : 4; }
@@ -548,19 +584,39 @@ template <int DTI, int DTO, int VEC>
 static hipError_t merge_dispatch(const StreamArgs &a, hipStream_t s)
 {
     const dim3 grid(a.n_tiles), block(WG);
-    // element-wise variant always stages bits in LDS; the vector variant does so above KREG_MAX tasks
     const size_t lds = sign_bits_lds_bytes(a.n_tasks, VEC);
+    // the element-wise variant and more than KREG_MAX tasks take the any-count kernel
     if constexpr (VEC == 1) {
-        hipLaunchKernelGGL((merge_kernel<DTI, DTO, VEC, 0, MERGE_R>), grid, block, lds, s, a);
+        hipLaunchKernelGGL((merge_kernel<DTI, DTO, VEC, 0, MERGE_R, false>), grid, block, lds, s, a);
         return hipGetLastError();
     }
     const int kt = a.n_tasks > KREG_MAX ? 0 : a.n_tasks;
     switch (kt) {
-#define RANDES_CASE(K) case K: hipLaunchKernelGGL((merge_kernel<DTI, DTO, VEC, K, MERGE_R>), grid, block, lds, s, a); break;
+#define RANDES_CASE(K) case K: hipLaunchKernelGGL((merge_kernel<DTI, DTO, VEC, K, MERGE_R, false>), grid, block, lds, s, a); break;
     RANDES_CASE(1) RANDES_CASE(2) RANDES_CASE(3) RANDES_CASE(4)
     RANDES_CASE(5) RANDES_CASE(6) RANDES_CASE(7) RANDES_CASE(8)
 #undef RANDES_CASE
-    default: hipLaunchKernelGGL((merge_kernel<DTI, DTO, VEC, 0, MERGE_R>), grid, block, lds, s, a); break;
+    default: hipLaunchKernelGGL((merge_kernel<DTI, DTO, VEC, 0, MERGE_R, false>), grid, block, lds, s, a); break;
+    }
+    return hipGetLastError();
+}
+
+// weights in, deltas formed on the fly: twice the streams per task, so half the rows per burst
+template <int DTI, int DTO, int VEC>
+static hipError_t merge_weights_dispatch(const StreamArgs &a, hipStream_t s)
+{
+    const dim3 grid(a.n_tiles), block(WG);
+    const size_t lds = sign_bits_lds_bytes(a.n_tasks, VEC);
+    constexpr int R = MERGE_WEIGHTS_R;
+    if constexpr (VEC == 1) {
+        hipLaunchKernelGGL((merge_kernel<DTI, DTO, VEC, 0, R, true>), grid, block, lds, s, a);
+        return hipGetLastError();
+    }
+    switch (a.n_tasks) {
+    case 2: hipLaunchKernelGGL((merge_kernel<DTI, DTO, VEC, 2, R, true>), grid, block, lds, s, a); break;
+    case 4: hipLaunchKernelGGL((merge_kernel<DTI, DTO, VEC, 4, R, true>), grid, block, lds, s, a); break;
+    case 8: hipLaunchKernelGGL((merge_kernel<DTI, DTO, VEC, 8, R, true>), grid, block, lds, s, a); break;
+    default: hipLaunchKernelGGL((merge_kernel<DTI, DTO, VEC, 0, R, true>), grid, block, lds, s, a); break;
     }
     return hipGetLastError();
 }
@@ -578,6 +634,21 @@ hipError_t launch_merge(const StreamArgs &a, int vec, int dt_in, int dt_out, hip
     if (dt_in == DT_F32 && dt_out == DT_BF16) return merge_dispatch<DT_F32, DT_BF16, 1>(a, s);
     if (dt_in == DT_BF16 && dt_out == DT_F32) return merge_dispatch<DT_BF16, DT_F32, 1>(a, s);
     return merge_dispatch<DT_BF16, DT_BF16, 1>(a, s);
+}
+
+hipError_t launch_merge_weights(const StreamArgs &a, int vec, int dt_in, int dt_out, hipStream_t s)
+{
+    if (a.n_tiles == 0) return hipSuccess;
+    if (vec) {
+        if (dt_in == DT_F32 && dt_out == DT_F32) return merge_weights_dispatch<DT_F32, DT_F32, 4>(a, s);
+        if (dt_in == DT_F32 && dt_out == DT_BF16) return merge_weights_dispatch<DT_F32, DT_BF16, 4>(a, s);
+        if (dt_in == DT_BF16 && dt_out == DT_F32) return merge_weights_dispatch<DT_BF16, DT_F32, 8>(a, s);
+        return merge_weights_dispatch<DT_BF16, DT_BF16, 8>(a, s);
+    }
+    if (dt_in == DT_F32 && dt_out == DT_F32) return merge_weights_dispatch<DT_F32, DT_F32, 1>(a, s);
+    if (dt_in == DT_F32 && dt_out == DT_BF16) return merge_weights_dispatch<DT_F32, DT_BF16, 1>(a, s);
+    if (dt_in == DT_BF16 && dt_out == DT_F32) return merge_weights_dispatch<DT_BF16, DT_F32, 1>(a, s);
+    return merge_weights_dispatch<DT_BF16, DT_BF16, 1>(a, s);
 }
 
 template <int DTM, int DTB, int VEC>

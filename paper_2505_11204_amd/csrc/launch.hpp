@@ -11,6 +11,8 @@ constexpr int DT_F32 = 0, DT_BF16 = 1;
 
 // vec = 0 launches the element-wise variant (one column per lane).
 hipError_t launch_merge(const StreamArgs &a, int vec, int dt_in, int dt_out, hipStream_t s);
+// Same with weights as inputs: srcs holds, per slot layer, T fine-tuned pointers then T base pointers.
+hipError_t launch_merge_weights(const StreamArgs &a, int vec, int dt_in, int dt_out, hipStream_t s);
 hipError_t launch_retrieve(const StreamArgs &a, int vec, int dt_merged, int dt_base, int dt_out, hipStream_t s);
 hipError_t launch_update(const StreamArgs &a, int vec, int dt_merged, int dt_delta, hipStream_t s);
 hipError_t launch_sign_mask(uint32_t key_lo, uint32_t key_hi, uint32_t layer, int64_t cols,
@@ -41,6 +43,7 @@ int update_vec(int dt_merged, int dt_delta);
 
 // Rows of a tile one wave handles in its single load burst (the kernels' compile-time R).
 int merge_burst_rows();
+int merge_weights_burst_rows();
 int two_input_burst_rows();
 
 // Plain streaming probe: out = sum of n_inputs streams (write != 0) or loads only (write == 0).

@@ -56,7 +56,7 @@ struct HostPlan {
     std::vector<uint32_t> keys;
 };
 
-enum PlanKind { PLAN_MERGE = 1, PLAN_RETRIEVE = 2, PLAN_UPDATE = 3 };
+enum PlanKind { PLAN_MERGE = 1, PLAN_RETRIEVE = 2, PLAN_UPDATE = 3, PLAN_MERGE_WEIGHTS = 4 };
 
 int validate_layers(const randes_layer *layers, int32_t n_layers, std::string *why);
 

@@ -353,3 +353,19 @@ def test_fused_lora_merge(dt_ab, dt_out, rank, n_tasks):
             # each of the n_tasks intermediate roundings is at most half a bf16 ulp of its own L_i
             bound = n_tasks * 2.0 ** -8 * max(d[l].float().abs().max().item() for d in deltas) + 2.0 ** -7 * b.abs().max().item()
             assert ((a - b).abs() <= bound).all()
+
+
+@pytest.mark.parametrize("dt,dt_merged", [("f32", "f32"), ("bf16", "bf16"), ("bf16", "f32")])
+@pytest.mark.parametrize("n_tasks", [1, 3, 4, 8, 11])
+def test_merge_from_weights(dt, dt_merged, n_tasks):
+    stack = ragged_stack()
+    layers = layers_of(stack)
+    seeds = [42 + i for i in range(n_tasks)]
+    base, deltas = cpu_inputs(stack, n_tasks, "f32")
+    weights = [[(b + d).to(TD[dt]) for b, d in zip(base, per)] for per in deltas]
+    base = [b.to(TD[dt]) for b in base]
+    got = rb.merge_weights(layers, [to_gpu(w) for w in weights], to_gpu(base), seeds, merged_dtype=TD[dt_merged])
+    want = oracle.merge_weights(layers, [np_lists(w) for w in weights], np_lists(base), seeds,
+                                CODE[dt], CODE[dt_merged], n_threads=8)
+    for l in range(len(stack)):
+        compare(got[l], want[l], "merge from weights, layer %d" % l)

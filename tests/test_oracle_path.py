@@ -354,3 +354,30 @@ def test_threads_do_not_change_the_result():
     b = oracle.merge(layers, deltas, seeds, n_threads=4)
     for l in range(3):
         assert np.array_equal(a[l].view(np.uint32), b[l].view(np.uint32))
+
+
+def test_merge_from_weights_equals_merge_of_float32_deltas():
+    # Delta_i = Theta_i - Theta_0 (Sec. 3), formed in binary32: identical to merging the numpy
+    # float32 differences; for bf16 weights the difference is NOT rounded back to bf16
+    layers = [(5, 40, 0, SRSF)] * 3 + [(2, 9, -1, FLIP)]
+    rng = np.random.default_rng(12)
+    seeds = [3, 4, 5]
+    base = [rng.standard_normal((m, n)).astype(np.float32) * 0.02 for (m, n, _, _) in layers]
+    weights = [[b + rng.standard_normal(b.shape).astype(np.float32) * 1e-3 for b in base] for _ in seeds]
+    deltas = [[w - b for w, b in zip(per, base)] for per in weights]
+    a = oracle.merge_weights(layers, weights, base, seeds)
+    b_ = oracle.merge(layers, deltas, seeds)
+    for l in range(len(layers)):
+        assert np.array_equal(a[l].view(np.uint32), b_[l].view(np.uint32))
+    base16 = [oracle.f32_to_bf16(x) for x in base]
+    w16 = [[oracle.f32_to_bf16(x) for x in per] for per in weights]
+    d32 = [[oracle.bf16_to_f32(w) - oracle.bf16_to_f32(b) for w, b in zip(per, base16)] for per in w16]
+    a16 = oracle.merge_weights(layers, w16, base16, seeds, BF16, BF16)
+    b16 = oracle.merge(layers, d32, seeds, F32, BF16)
+    for l in range(len(layers)):
+        assert np.array_equal(a16[l], b16[l])
+    # the base that is subtracted is the one of the SOURCE layer (it travels with the shuffle):
+    # with every model equal to the base the result is exactly zero whatever the permutation
+    z = oracle.merge_weights(layers, [base, base], base, [1, 2])
+    for l in range(len(layers)):
+        assert (z[l] == 0).all()
