@@ -146,6 +146,21 @@ int randes_update(const randes_layer *layers, int32_t n_layers,
                   const void *const *delta, randes_dtype delta_dtype,
                   uint64_t seed, int32_t remove, void *hip_stream);
 
+/* Diagnostics of Sec. 3 ("Interference in Model Merging") on the device: inner product and squared
+ * norms of two transformed deltas over a whole stack, in binary64,
+ *   a'[l] = D_a^l-flipped delta_a[src_a(l)],   b'[l] = D_b^l-flipped delta_b[src_b(l)]
+ *   out3 = { <a', b'>, <a', a'>, <b', b'> }          (out3: DEVICE array of 3 doubles)
+ * from which follow the pairwise cosine similarity of (interfering) deltas and the interference norm
+ * identity || sum_j Delta_j ||^2 = sum_j ||Delta_j||^2 + 2 sum_{l<j} <Delta_l, Delta_j>.  Pass layers with
+ * flags = 0 for the untransformed deltas.  The common factor D_i^-1 of a retrieval is orthogonal and
+ * drops out of every inner product, so it is not needed here.  Work proceeds through per-workgroup
+ * partial sums kept inside the cached tables and summed in a fixed order: the result is reproducible,
+ * and two calls with identical arguments on different streams at the same time would race on them. */
+int randes_delta_stats(const randes_layer *layers, int32_t n_layers,
+                       const void *const *delta_a, uint64_t seed_a,
+                       const void *const *delta_b, uint64_t seed_b,
+                       randes_dtype dtype, double *out3, void *hip_stream);
+
 /* LoRA front-end (Sec. "Parameter Efficient Finetuning (PEFT) Model Compression":
  * Theta_i = Theta_0 + lambda L_i): materialise the dense adapter update
  *   delta_out[r][c] = scale * sum_{t < rank} B[r][t] * A[t][c]

@@ -89,6 +89,9 @@ def lib():
         L.oracle_dot3.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int,
                                   ctypes.c_void_p]
         L.oracle_dot3.restype = None
+        L.oracle_delta_stats.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_uint64,
+                                         ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int, ctypes.c_void_p]
+        L.oracle_delta_stats.restype = ctypes.c_int
         L.oracle_max_threads.argtypes = []
         L.oracle_max_threads.restype = ctypes.c_int
         _lib = L
@@ -271,6 +274,19 @@ def dot3(a, b, dtype=F32):
     _check(b, dtype, a.size)
     out = (ctypes.c_double * 3)()
     lib().oracle_dot3(a.ctypes.data, b.ctypes.data, a.size, dtype, out)
+    return float(out[0]), float(out[1]), float(out[2])
+
+
+def delta_stats(layers, a, seed_a, b, seed_b, dtype=F32):
+    """(<a',b'>, <a',a'>, <b',b'>) of two transformed deltas (lists of per-layer arrays)."""
+    n_layers = len(layers)
+    aa = [_check(a[l], dtype, layers[l][0] * layers[l][1]) for l in range(n_layers)]
+    bb = [_check(b[l], dtype, layers[l][0] * layers[l][1]) for l in range(n_layers)]
+    out = (ctypes.c_double * 3)()
+    rc = lib().oracle_delta_stats(_layers_struct(layers), n_layers, _ptr_array(aa), int(seed_a) & 0xFFFFFFFFFFFFFFFF,
+                                  _ptr_array(bb), int(seed_b) & 0xFFFFFFFFFFFFFFFF, dtype, out)
+    if rc != 0:
+        raise ValueError("shape mismatch inside a shuffle group")
     return float(out[0]), float(out[1]), float(out[2])
 
 

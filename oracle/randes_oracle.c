@@ -466,6 +466,45 @@ void oracle_dot3(const void *a, const void *b, int64_t count, int dtype, double 
     out3[0] = ab; out3[1] = aa; out3[2] = bb;
 }
 
+/* ------------------------------------------------------------------------
+ * The same three sums for two transformed deltas over a whole stack:
+ *     a'[l] = D_a^l-flipped a[src_a(l)],  b'[l] = D_b^l-flipped b[src_b(l)],
+ * out3 = { <a',b'>, <a',a'>, <b',b'> } accumulated in binary64 in layer, row,
+ * column order.  This is the "pairwise cosine similarity among interfering
+ * deltas" of the experiments: the retrieving model's own D^-1 is orthogonal
+ * and drops out of every inner product.
+ * ---------------------------------------------------------------------- */
+int oracle_delta_stats(const oracle_layer *layers, int32_t n_layers,
+                       const void *const *a, uint64_t seed_a, const void *const *b, uint64_t seed_b,
+                       int dtype, double out3[3])
+{
+    int32_t *sa = (int32_t *)malloc(sizeof(int32_t) * (size_t)n_layers);
+    int32_t *sb = (int32_t *)malloc(sizeof(int32_t) * (size_t)n_layers);
+    if (oracle_source_table(layers, n_layers, &seed_a, 1, sa) != 0 ||
+        oracle_source_table(layers, n_layers, &seed_b, 1, sb) != 0) { free(sa); free(sb); return -1; }
+    double ab = 0.0, aa = 0.0, bb = 0.0;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        const int64_t m = layers[l].rows, n = layers[l].cols;
+        uint8_t *ma = (uint8_t *)calloc((size_t)n, 1), *mb = (uint8_t *)calloc((size_t)n, 1);
+        if (layers[l].flags & ORACLE_FLIP) {
+            oracle_sign_mask(seed_a, (uint32_t)l, n, ma);
+            oracle_sign_mask(seed_b, (uint32_t)l, n, mb);
+        }
+        for (int64_t r = 0; r < m; ++r)
+            for (int64_t c = 0; c < n; ++c) {
+                double x = (double)load_elem(a[sa[l]], r * n + c, dtype);
+                double y = (double)load_elem(b[sb[l]], r * n + c, dtype);
+                if (ma[c]) x = -x;
+                if (mb[c]) y = -y;
+                ab += x * y; aa += x * x; bb += y * y;
+            }
+        free(ma); free(mb);
+    }
+    out3[0] = ab; out3[1] = aa; out3[2] = bb;
+    free(sa); free(sb);
+    return 0;
+}
+
 int oracle_max_threads(void)
 {
 #ifdef _OPENMP

@@ -48,6 +48,7 @@ struct CachedPlan {
     std::string key;
     int device = 0;
     void *blob = nullptr;     // device tables
+    void *extra = nullptr;    // scratch inside the blob (stats partials)
     StreamArgs vec{}, scl{};
 };
 
@@ -84,6 +85,8 @@ int upload(HostPlan &hp, int n_tasks, CachedPlan *cp)
     }
     const size_t off_keys = off;
     off = pad(off + hp.keys.size() * sizeof(uint32_t));
+    const size_t off_extra = off;
+    off = pad(off + hp.extra_bytes);
     std::vector<char> host(off, 0);
     for (int s = 0; s < 2; ++s) {
         if (!sub[s]->layers.empty()) memcpy(host.data() + off_layers[s], sub[s]->layers.data(), sub[s]->layers.size() * sizeof(LayerDev));
@@ -96,6 +99,7 @@ int upload(HostPlan &hp, int n_tasks, CachedPlan *cp)
     if (e != hipSuccess) return hip_fail(e, "hipMalloc(plan tables)");
     e = hipMemcpy(cp->blob, host.data(), off, hipMemcpyHostToDevice);
     if (e != hipSuccess) { (void)hipFree(cp->blob); cp->blob = nullptr; return hip_fail(e, "hipMemcpy(plan tables)"); }
+    cp->extra = hp.extra_bytes ? (char *)cp->blob + off_extra : nullptr;
     StreamArgs *args[2] = { &cp->vec, &cp->scl };
     for (int s = 0; s < 2; ++s) {
         StreamArgs &a = *args[s];
@@ -453,6 +457,73 @@ int randes_update(const randes_layer *layers, int32_t n_layers,
     if (e != hipSuccess) return hip_fail(e, "update launch");
     e = launch_update(as, 0, merged_dtype, delta_dtype, s);
     if (e != hipSuccess) return hip_fail(e, "update launch (element-wise)");
+    return RANDES_OK;
+}
+
+int randes_delta_stats(const randes_layer *layers, int32_t n_layers,
+                       const void *const *delta_a, uint64_t seed_a,
+                       const void *const *delta_b, uint64_t seed_b,
+                       randes_dtype dtype, double *out3, void *hip_stream)
+{
+    std::string why;
+    int rc = validate_layers(layers, n_layers, &why);
+    if (rc) return fail(rc, why);
+    if (!delta_a || !delta_b || !out3) return fail(RANDES_EINVAL, "delta_a, delta_b or out3 is NULL");
+    if (!dtype_ok(dtype)) return fail(RANDES_EINVAL, "unknown dtype");
+    for (int32_t l = 0; l < n_layers; ++l)
+        if (!delta_a[l] || !delta_b[l]) return fail(RANDES_EINVAL, "NULL layer pointer");
+    int dev;
+    if ((rc = current_device(&dev))) return rc;
+    std::string key;
+    const int32_t head[4] = { PLAN_STATS, n_layers, (int32_t)dtype, g_retrieve_rows * 4 + g_max_wx_shift };
+    append(&key, head, sizeof(head));
+    append(&key, layers, sizeof(randes_layer) * (size_t)n_layers);
+    append(&key, delta_a, sizeof(void *) * (size_t)n_layers);
+    append(&key, delta_b, sizeof(void *) * (size_t)n_layers);
+    append(&key, &seed_a, sizeof(seed_a));
+    append(&key, &seed_b, sizeof(seed_b));
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    CachedPlan *cp = lookup(key, dev);
+    if (!cp) {
+        HostPlan hp;
+        std::vector<int32_t> sa, sb;
+        if ((rc = build_source_table(layers, n_layers, seed_a, &sa, &why))) return fail(rc, why);
+        if ((rc = build_source_table(layers, n_layers, seed_b, &sb, &why))) return fail(rc, why);
+        const int vec = stats_vec(dtype);
+        for (int32_t l = 0; l < n_layers; ++l) {
+            LayerDev d{};
+            d.a = delta_a[sa[(size_t)l]];
+            d.b = delta_b[sb[(size_t)l]];
+            d.rows = (int32_t)layers[l].rows;
+            d.cols = (int32_t)layers[l].cols;
+            d.layer_id = (uint32_t)l;
+            d.flip = (layers[l].flags & RANDES_FLIP) ? 1u : 0u;
+            const bool vector_ok = (layers[l].cols % vec) == 0 && aligned16(d.a) && aligned16(d.b);
+            if ((rc = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(g_retrieve_rows, two_input_burst_rows())))) return rc;
+        }
+        hp.extra_bytes = ((size_t)hp.vec.n_tiles + hp.scl.n_tiles) * 3 * sizeof(double);
+        CachedPlan fresh;
+        fresh.key = key;
+        fresh.device = dev;
+        if ((rc = upload(hp, 1, &fresh))) return rc;
+        cp = insert_plan(std::move(fresh));
+    }
+    StreamArgs av = cp->vec, as = cp->scl;
+    av.key_lo = as.key_lo = (uint32_t)(seed_a & 0xffffffffu);
+    av.key_hi = as.key_hi = (uint32_t)(seed_a >> 32);
+    av.key2_lo = as.key2_lo = (uint32_t)(seed_b & 0xffffffffu);
+    av.key2_hi = as.key2_hi = (uint32_t)(seed_b >> 32);
+    av.partials = as.partials = (double *)cp->extra;
+    av.partial_base = 0;
+    as.partial_base = av.n_tiles;
+    hipStream_t s = (hipStream_t)hip_stream;
+    hipError_t e = launch_stats(av, 1, dtype, s);
+    if (e != hipSuccess) return hip_fail(e, "stats launch");
+    e = launch_stats(as, 0, dtype, s);
+    if (e != hipSuccess) return hip_fail(e, "stats launch (element-wise)");
+    e = launch_stats_finalize((const double *)cp->extra, av.n_tiles + as.n_tiles, out3, s);
+    if (e != hipSuccess) return hip_fail(e, "stats finalize launch");
     return RANDES_OK;
 }
 

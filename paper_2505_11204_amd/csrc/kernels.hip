@@ -491,6 +491,92 @@ __global__ void __launch_bounds__(WG) update_kernel(const StreamArgs A)
     two_input_bursts<DTD, DTM, DTM, VEC, false>(A, t, (gcptr)t.L.a, (gcptr)t.L.dst, (gptr)t.L.dst, sbits);
 }
 
+// ---------------------------------------------------------------------------
+// Diagnostics of Sec. 3 ("Interference in Model Merging"): inner product and squared norms of two
+// transformed deltas a' = D_a-flipped a[src_a(l)], b' = D_b-flipped b[src_b(l)] over a whole stack,
+// in binary64.  Same burst shape as retrieve (two read streams, no write stream); each workgroup
+// leaves one triple in `partials`, summed afterwards in a fixed order, so the result does not
+// depend on scheduling.
+// ---------------------------------------------------------------------------
+template <int DT, int VEC>
+__global__ void __launch_bounds__(WG) stats_kernel(const StreamArgs A)
+{
+    constexpr uint32_t EB = (DT == DT_F32) ? 4 : 2;
+    constexpr int NW = NumWords<DT, VEC>::value;
+    constexpr int R = TWO_INPUT_R;
+    extern __shared__ uint32_t sbits[];
+    __shared__ double swave[WAVES][3];
+    const Tile t = locate<VEC>(A);
+    const uint32_t cols = (uint32_t)t.L.cols;
+    const gcptr pa = (gcptr)t.L.a + (size_t)t.row0 * cols * EB;
+    const gcptr pb = (gcptr)t.L.b + (size_t)t.row0 * cols * EB;
+    const uint32_t e = t.wy * cols + t.col, estep = t.WY * cols;
+    const uint32_t r = t.row0 + t.wy;
+    uint32_t ra[R][NW], rb[R][NW];
+    if (t.active) {
+#pragma unroll
+        for (int u = 0; u < R; ++u)
+            if (r + t.WY * u < t.row_end) {
+                load_raw<DT, VEC>(pa + (e + u * estep) * EB, ra[u]);
+                load_raw<DT, VEC>(pb + (e + u * estep) * EB, rb[u]);
+            }
+    }
+    const uint32_t nblk = stage_sign_bits(sbits, t, nullptr, 1u, A.key_lo, A.key_hi);
+    stage_sign_bits(sbits + nblk * 4u, t, nullptr, 1u, A.key2_lo, A.key2_hi);
+    lds_barrier();
+    double s_ab = 0.0, s_aa = 0.0, s_bb = 0.0;
+    if (t.active) {
+        const uint32_t bits = lane_bits_from_lds<VEC>(sbits, t, nblk, 0u) ^ lane_bits_from_lds<VEC>(sbits + nblk * 4u, t, nblk, 0u);
+#pragma unroll
+        for (int u = 0; u < R; ++u)
+            if (r + t.WY * u < t.row_end) {
+                float x[VEC], y[VEC];
+                widen<DT, VEC>(ra[u], x);
+                widen<DT, VEC>(rb[u], y);
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    const double xa = (double)u2f(f2u(x[j]) ^ ((bits << (31 - j)) & 0x80000000u));   // both flips on a
+                    const double yb = (double)y[j];
+                    s_ab += xa * yb;
+                    s_aa += xa * xa;
+                    s_bb += yb * yb;
+                }
+            }
+    }
+    // lanes -> wave (fixed butterfly), waves -> workgroup (fixed order)
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        s_ab += __shfl_down(s_ab, off, 64);
+        s_aa += __shfl_down(s_aa, off, 64);
+        s_bb += __shfl_down(s_bb, off, 64);
+    }
+    const uint32_t wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63u) == 0) { swave[wave][0] = s_ab; swave[wave][1] = s_aa; swave[wave][2] = s_bb; }
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        double v = 0.0;
+        for (int w = 0; w < WAVES; ++w) v += swave[w][threadIdx.x];
+        A.partials[((size_t)A.partial_base + blockIdx.x) * 3u + threadIdx.x] = v;
+    }
+}
+
+// One workgroup: thread q sums partials q, q + 256, ... in order; then a fixed tree over the 256.
+__global__ void __launch_bounds__(WG) stats_finalize_kernel(const double *partials, uint32_t n_partials, double *out3)
+{
+    __shared__ double sh[WG][3];
+    double v[3] = {0.0, 0.0, 0.0};
+    for (uint32_t q = threadIdx.x; q < n_partials; q += WG)
+        for (int c = 0; c < 3; ++c) v[c] += partials[(size_t)q * 3u + c];
+    for (int c = 0; c < 3; ++c) sh[threadIdx.x][c] = v[c];
+    __syncthreads();
+    for (uint32_t half = WG / 2; half > 0; half >>= 1) {
+        if (threadIdx.x < half)
+            for (int c = 0; c < 3; ++c) sh[threadIdx.x][c] += sh[threadIdx.x + half][c];
+        __syncthreads();
+    }
+    if (threadIdx.x < 3) out3[threadIdx.x] = sh[0][threadIdx.x];
+}
+
 // One byte per column: 1 where D is -1.
 __global__ void __launch_bounds__(WG) sign_mask_kernel(uint32_t key_lo, uint32_t key_hi, uint32_t layer,
                                                        int64_t cols, uint8_t *mask_out)
@@ -698,6 +784,29 @@ hipError_t launch_update(const StreamArgs &a, int vec, int dt_merged, int dt_del
     case 6: return update_dispatch<DT_BF16, DT_F32, 8>(a, s);
     default: return update_dispatch<DT_BF16, DT_BF16, 8>(a, s);
     }
+}
+
+int stats_vec(int dt) { return dt == DT_BF16 ? 8 : 4; }
+
+hipError_t launch_stats(const StreamArgs &a, int vec, int dt, hipStream_t s)
+{
+    if (a.n_tiles == 0) return hipSuccess;
+    const dim3 grid(a.n_tiles), block(WG);
+    const size_t lds = 2 * sign_bits_lds_bytes(1, vec ? stats_vec(dt) : 1);
+    if (vec) {
+        if (dt == DT_F32) hipLaunchKernelGGL((stats_kernel<DT_F32, 4>), grid, block, lds, s, a);
+        else hipLaunchKernelGGL((stats_kernel<DT_BF16, 8>), grid, block, lds, s, a);
+    } else {
+        if (dt == DT_F32) hipLaunchKernelGGL((stats_kernel<DT_F32, 1>), grid, block, lds, s, a);
+        else hipLaunchKernelGGL((stats_kernel<DT_BF16, 1>), grid, block, lds, s, a);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_stats_finalize(const double *partials, uint32_t n_partials, double *out3, hipStream_t s)
+{
+    hipLaunchKernelGGL(stats_finalize_kernel, dim3(1), dim3(WG), 0, s, partials, n_partials, out3);
+    return hipGetLastError();
 }
 
 hipError_t launch_sign_mask(uint32_t key_lo, uint32_t key_hi, uint32_t layer, int64_t cols,

@@ -15,6 +15,10 @@ hipError_t launch_merge(const StreamArgs &a, int vec, int dt_in, int dt_out, hip
 hipError_t launch_merge_weights(const StreamArgs &a, int vec, int dt_in, int dt_out, hipStream_t s);
 hipError_t launch_retrieve(const StreamArgs &a, int vec, int dt_merged, int dt_base, int dt_out, hipStream_t s);
 hipError_t launch_update(const StreamArgs &a, int vec, int dt_merged, int dt_delta, hipStream_t s);
+// stats: per-workgroup partial triples into a.partials, then stats_finalize sums n_partials of them
+// in a fixed order into out3 = { <a',b'>, <a',a'>, <b',b'> }.
+hipError_t launch_stats(const StreamArgs &a, int vec, int dt, hipStream_t s);
+hipError_t launch_stats_finalize(const double *partials, uint32_t n_partials, double *out3, hipStream_t s);
 hipError_t launch_sign_mask(uint32_t key_lo, uint32_t key_hi, uint32_t layer, int64_t cols,
                             uint8_t *mask_out, hipStream_t s);
 
@@ -42,6 +46,7 @@ int retrieve_vec(int dt_merged, int dt_base);
 int update_vec(int dt_merged, int dt_delta);
 
 // Rows of a tile one wave handles in its single load burst (the kernels' compile-time R).
+int stats_vec(int dt);
 int merge_burst_rows();
 int merge_weights_burst_rows();
 int two_input_burst_rows();

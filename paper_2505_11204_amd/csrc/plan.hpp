@@ -40,6 +40,9 @@ struct StreamArgs {
     uint32_t key_lo, key_hi;      // retrieve / update: the one model's seed
     float lambda;                 // retrieve
     uint32_t negate;              // update: 1 removes the model
+    uint32_t key2_lo, key2_hi;    // stats: the second model's seed
+    double *partials;             // stats: one triple per workgroup
+    uint32_t partial_base;        // stats: index of this launch's first triple
 };
 
 // A sub-plan: the layers one kernel variant handles (vector or element-wise).
@@ -54,9 +57,10 @@ struct SubPlan {
 struct HostPlan {
     SubPlan vec, scl;
     std::vector<uint32_t> keys;
+    size_t extra_bytes = 0;   // scratch appended to the device tables (stats: per-workgroup partials)
 };
 
-enum PlanKind { PLAN_MERGE = 1, PLAN_RETRIEVE = 2, PLAN_UPDATE = 3, PLAN_MERGE_WEIGHTS = 4 };
+enum PlanKind { PLAN_MERGE = 1, PLAN_RETRIEVE = 2, PLAN_UPDATE = 3, PLAN_MERGE_WEIGHTS = 4, PLAN_STATS = 5 };
 
 int validate_layers(const randes_layer *layers, int32_t n_layers, std::string *why);
 

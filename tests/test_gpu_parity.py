@@ -369,3 +369,29 @@ def test_merge_from_weights(dt, dt_merged, n_tasks):
                                 CODE[dt], CODE[dt_merged], n_threads=8)
     for l in range(len(stack)):
         compare(got[l], want[l], "merge from weights, layer %d" % l)
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_delta_stats(dt):
+    stack = ragged_stack()
+    layers = layers_of(stack)
+    _, deltas = cpu_inputs(stack, 2, dt, delta_std=1.0)
+    ga, gb = to_gpu(deltas[0]), to_gpu(deltas[1])
+    na, nb = np_lists(deltas[0]), np_lists(deltas[1])
+    for (sa, sb, lay) in ((42, 43, layers), (42, 42, layers), (1, 2, [(m, n, g, 0) for (m, n, g, _) in layers])):
+        got = rb.delta_stats(lay, ga, sa, gb, sb).cpu().numpy()
+        want = np.array(oracle.delta_stats(lay, na, sa, nb, sb, CODE[dt]))
+        scale = np.sqrt(want[1] * want[2])
+        assert np.all(np.abs(got - want) <= 1e-11 * scale), (got, want)
+    # decorrelation: identical deltas under different seeds are nearly orthogonal, under equal seeds parallel
+    # (on layers that all carry the flip; the ragged stack has an unflagged layer that stays correlated)
+    flagged = [(64, 2048, 0, SRSF)] * 4
+    _, fd = cpu_inputs([Layer(*l) for l in flagged], 1, dt, delta_std=1.0)
+    gf = to_gpu(fd[0])
+    c_diff = rb.delta_stats(flagged, gf, 42, gf, 43).cpu().numpy()
+    c_same = rb.delta_stats(flagged, gf, 42, gf, 42).cpu().numpy()
+    assert abs(c_same[0] / np.sqrt(c_same[1] * c_same[2]) - 1.0) < 1e-12
+    assert abs(c_diff[0] / np.sqrt(c_diff[1] * c_diff[2])) < 0.05
+    # reproducible bit for bit
+    again = rb.delta_stats(flagged, gf, 42, gf, 43).cpu().numpy()
+    assert np.array_equal(again.view(np.uint64), c_diff.view(np.uint64))

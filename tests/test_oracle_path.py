@@ -381,3 +381,33 @@ def test_merge_from_weights_equals_merge_of_float32_deltas():
     z = oracle.merge_weights(layers, [base, base], base, [1, 2])
     for l in range(len(layers)):
         assert (z[l] == 0).all()
+
+
+def test_delta_stats_against_numpy_and_the_merge_itself():
+    layers = [(4, 33, 0, SRSF)] * 3 + [(3, 10, -1, FLIP)]
+    rng = np.random.default_rng(13)
+    a = [rng.standard_normal((m, n)).astype(np.float32) for (m, n, _, _) in layers]
+    b = [rng.standard_normal((m, n)).astype(np.float32) for (m, n, _, _) in layers]
+    sa, sb = 21, 22
+    ab, aa, bb = oracle.delta_stats(layers, a, sa, b, sb)
+    # explicit: transformed copies through the single-model merge (already pinned), then numpy
+    ta = oracle.merge(layers, [a], [sa])
+    tb = oracle.merge(layers, [b], [sb])
+    fa = np.concatenate([x.reshape(-1).astype(np.float64) for x in ta])
+    fb = np.concatenate([x.reshape(-1).astype(np.float64) for x in tb])
+    assert abs(ab - fa @ fb) < 1e-10 and abs(aa - fa @ fa) < 1e-10 and abs(bb - fb @ fb) < 1e-10
+    # orthogonal transforms keep norms: same as the untransformed norms
+    ra = np.concatenate([x.reshape(-1).astype(np.float64) for x in a])
+    assert abs(aa - ra @ ra) < 1e-10
+    # the same transform on both sides keeps the inner product (O_i^T O_i = I)
+    ab_same, _, _ = oracle.delta_stats(layers, a, sa, b, sa)
+    rb_ = np.concatenate([x.reshape(-1).astype(np.float64) for x in b])
+    assert abs(ab_same - ra @ rb_) < 1e-10
+    # no flags: plain inner products
+    plain = [(m, n, g, 0) for (m, n, g, _) in layers]
+    ab0, aa0, bb0 = oracle.delta_stats(plain, a, sa, b, sb)
+    assert abs(ab0 - ra @ rb_) < 1e-10
+    # Sec. 3 norm identity through these sums: ||a' + b'||^2 = aa + bb + 2 ab
+    m2 = oracle.merge(layers, [a, b], [sa, sb])
+    fm = np.concatenate([x.reshape(-1).astype(np.float64) for x in m2])
+    assert abs(fm @ fm - (aa + bb + 2 * ab)) < 1e-4 * (aa + bb)   # merge rounds to float32
