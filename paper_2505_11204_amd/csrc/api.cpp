@@ -539,25 +539,36 @@ int run_lora(std::vector<LoraItem> &items, const std::vector<LoraSeg> &segs, int
     for (LoraItem &it : items) {
         it.tiles_x = (uint32_t)(((int64_t)it.cols + LORA_TILE_N - 1) / LORA_TILE_N);
         it.tile_begin = (uint32_t)tiles;
-        tiles += (uint64_t)it.tiles_x * (uint64_t)(((int64_t)it.rows + LORA_TILE_M - 1) / LORA_TILE_M);
+        tiles += (uint64_t)it.tiles_x * (uint64_t)(((int64_t)it.rows + LORA_TILE_M * LORA_ROW_TILES - 1) / (LORA_TILE_M * LORA_ROW_TILES));
         if (tiles >= ((uint64_t)1 << 31)) return fail(RANDES_ENOTSUP, "too many tiles for one launch");
     }
     int dev, rc;
     if ((rc = current_device(&dev))) return rc;
     const size_t items_bytes = (sizeof(LoraItem) * items.size() + 255) & ~(size_t)255;
-    const size_t segs_bytes = sizeof(LoraSeg) * segs.size();
+    const size_t segs_bytes = (sizeof(LoraSeg) * segs.size() + 255) & ~(size_t)255;
+    std::vector<uint32_t> coarse;
+    {
+        uint32_t item = 0;
+        const uint64_t n_chunks = (tiles + 63) / 64;
+        for (uint64_t i = 0; i <= n_chunks; ++i) {
+            const uint64_t tile = std::min<uint64_t>(i * 64, tiles - 1);
+            while (item + 1 < items.size() && items[item + 1].tile_begin <= tile) ++item;
+            coarse.push_back(item);
+        }
+    }
     std::string key;
     const int32_t head[3] = { 100, (int32_t)items.size(), (int32_t)segs.size() };
     append(&key, head, sizeof(head));
     append(&key, items.data(), sizeof(LoraItem) * items.size());
-    append(&key, segs.data(), segs_bytes);
+    append(&key, segs.data(), sizeof(LoraSeg) * segs.size());
 
     std::lock_guard<std::mutex> lock(g_mu);
     CachedPlan *cp = lookup(key, dev);
     if (!cp) {
-        std::vector<char> host(items_bytes + segs_bytes, 0);
+        std::vector<char> host(items_bytes + segs_bytes + coarse.size() * sizeof(uint32_t), 0);
         memcpy(host.data(), items.data(), sizeof(LoraItem) * items.size());
-        memcpy(host.data() + items_bytes, segs.data(), segs_bytes);
+        memcpy(host.data() + items_bytes, segs.data(), sizeof(LoraSeg) * segs.size());
+        memcpy(host.data() + items_bytes + segs_bytes, coarse.data(), coarse.size() * sizeof(uint32_t));
         CachedPlan fresh;
         fresh.key = key;
         fresh.device = dev;
@@ -568,7 +579,8 @@ int run_lora(std::vector<LoraItem> &items, const std::vector<LoraSeg> &segs, int
         cp = insert_plan(std::move(fresh));
     }
     hipError_t e = launch_lora((const LoraItem *)cp->blob, (int32_t)items.size(),
-                               (const LoraSeg *)((const char *)cp->blob + items_bytes), (uint32_t)tiles, rank, scale,
+                               (const LoraSeg *)((const char *)cp->blob + items_bytes),
+                               (const uint32_t *)((const char *)cp->blob + items_bytes + segs_bytes), (uint32_t)tiles, rank, scale,
                                ab_dtype, out_dtype, (hipStream_t)hip_stream);
     if (e != hipSuccess) return hip_fail(e, "lora launch");
     return RANDES_OK;

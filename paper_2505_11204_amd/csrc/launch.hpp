@@ -36,8 +36,9 @@ struct LoraSeg {
     const void *A;        // rank x cols
     uint32_t key_lo, key_hi, layer_id, flip;   // the sign diagonal D (flip = 0: identity)
 };
-hipError_t launch_lora(const LoraItem *items_dev, int32_t n_items, const LoraSeg *segs_dev, uint32_t n_tiles,
-                       int32_t rank, float scale, int dt_ab, int dt_out, hipStream_t s);
+// coarse_dev[i] = matrix holding workgroup 64 * i, for i = 0 .. ceil(n_tiles / 64).
+hipError_t launch_lora(const LoraItem *items_dev, int32_t n_items, const LoraSeg *segs_dev, const uint32_t *coarse_dev,
+                       uint32_t n_tiles, int32_t rank, float scale, int dt_ab, int dt_out, hipStream_t s);
 
 // Columns per lane of the vector kernels for a call whose widest-count stream
 // holds bf16 (8) or only f32 (4).
@@ -57,6 +58,6 @@ constexpr uint64_t PROBE_CHUNK_BYTES = 4u * 256u * 16u;
 hipError_t launch_probe(const void *const *inputs, int n_inputs, void *output, uint64_t bytes, int write, hipStream_t s);
 
 // Workgroup tile of the LoRA kernel.
-constexpr int LORA_TILE_M = 32, LORA_TILE_N = 512;
+constexpr int LORA_TILE_M = 32, LORA_TILE_N = 512, LORA_ROW_TILES = 4;
 
 }  // namespace randes

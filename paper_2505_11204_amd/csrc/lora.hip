@@ -7,8 +7,9 @@
 // with the sign diagonal D of its model, is the superposition of K adapters written once:
 // sum_i (B_i A_i) D_i = [B_1 .. B_K] [A_1 D_1; ..; A_K D_K], a rank K*r contraction.
 //
-// A workgroup (4 waves) owns 32 rows x 512 columns; each wave owns 32 x 128 = four 32x32 MFMA
-// accumulators.  Per 16-deep slice of the rank the workgroup stages A's 16 x 512 slab, sign-flipped,
+// A workgroup (4 waves) owns 512 columns and LORA_ROW_TILES consecutive blocks of 32 rows; per block
+// each wave owns 32 x 128 = four 32x32 MFMA accumulators.  With a single segment of rank <= 16 the
+// staged slab of A serves all row blocks of the workgroup.  Per 16-deep slice of the rank the workgroup stages A's 16 x 512 slab, sign-flipped,
 // into LDS with 16-byte accesses (row-major, as in memory); a lane then gathers the 8 depth values
 // of its column with 2-byte LDS reads, which are conflict-free because neighbouring lanes read
 // neighbouring columns.  B's rows come straight from global memory (16 bytes per lane).  bf16
@@ -17,7 +18,10 @@
 //
 // Operand layout of the 32x32 MFMAs: lane L supplies row (L % 32) of the left operand and column
 // (L % 32) of the right operand for the depth slice owned by lane half (L / 32); accumulator
-// register v of lane L is output row 8*(v/4) + 4*(L/32) + (v%4), column L % 32.
+// register v of lane L is row 8*(v/4) + 4*(L/32) + (v%4), column L % 32 of the product.  For bf16
+// output the product is formed transposed (A^T-slice as left operand, B^T as right), so that a lane
+// ends up with four adjacent output columns per accumulator quad and can hand them to LDS 8 bytes
+// at a time.
 #include <hip/hip_runtime.h>
 
 #include "device_util.hpp"
@@ -35,16 +39,18 @@ constexpr int ST_STRIDE = 136;          // bf16 elements per staged output row (
 
 template <int DTAB, int DTO>
 __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t n_items, const LoraSeg *segs,
-                                                  int32_t rank, float scale)
+                                                  const uint32_t *coarse, int32_t rank, float scale)
 {
     constexpr int AT_BYTES = KCH * AS_STRIDE * (DTAB == DT_BF16 ? 2 : 4);
-    constexpr int ST_BYTES = WAVES * LORA_TILE_M * ST_STRIDE * 2;
-    constexpr int SMEM = AT_BYTES > ST_BYTES ? AT_BYTES : ST_BYTES;
-    __shared__ __attribute__((aligned(16))) char smem[SMEM];
+    constexpr int ST_BYTES = (DTO == DT_BF16) ? WAVES * LORA_TILE_M * ST_STRIDE * 2 : 16;
+    __shared__ __attribute__((aligned(16))) char smem[AT_BYTES];       // the staged slab of A
+    __shared__ __attribute__((aligned(16))) char sstage[ST_BYTES];     // bf16 output staging, one region per wave
     __shared__ uint32_t sbits[LORA_TILE_N / 32];
 
     const uint32_t bid = blockIdx.x;
-    int lo = 0, hi = n_items;
+    // coarse[i] = matrix that holds workgroup 64 * i: narrows the search to a step or two
+    int lo = (int)coarse[bid >> 6], hi = (int)coarse[(bid >> 6) + 1] + 1;
+    if (hi > n_items) hi = n_items;
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
         if (items[mid].tile_begin <= bid) lo = mid; else hi = mid;
@@ -55,8 +61,14 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
     const uint32_t tid = threadIdx.x;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t lane = tid & 63u, half = lane >> 5, l32 = lane & 31u;
-    const int32_t row0 = (int32_t)ty * LORA_TILE_M, col0 = (int32_t)tx * LORA_TILE_N;
+    const int32_t col0 = (int32_t)tx * LORA_TILE_N;
     const int32_t rows = it.rows, cols = it.cols;
+    const bool reuse_slab = (it.n_seg == 1) && (rank <= KCH);   // one staging serves every row block
+
+  for (int rt = 0; rt < LORA_ROW_TILES; ++rt) {
+    const int32_t row0 = ((int32_t)ty * LORA_ROW_TILES + rt) * LORA_TILE_M;
+    if (row0 >= rows) break;
+    const bool stage_now = !reuse_slab || rt == 0;
     const int32_t my_row = row0 + (int32_t)l32;              // left-operand row of this lane
     const bool row_ok = my_row < rows;
 
@@ -69,7 +81,7 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
     for (uint32_t sg = 0; sg < it.n_seg; ++sg) {
         const LoraSeg S = segs[it.seg_begin + sg];
         // sign bits of this tile's 512 columns: four generator blocks (tiles start on multiples of 512)
-        if (tid < LORA_TILE_N / 128) {
+        if (stage_now && tid < LORA_TILE_N / 128) {
             u32x4_t o;
             if (S.flip) o = sign_block(S.key_lo, S.key_hi, S.layer_id, ((uint32_t)col0 >> 7) + tid);
             else { o.w[0] = o.w[1] = o.w[2] = o.w[3] = 0u; }
@@ -80,6 +92,23 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
         const bool b_vec_ok = (rank % 8 == 0) && (((uintptr_t)S.B & 15u) == 0);
 
         for (int32_t k0 = 0; k0 < rank; k0 += KCH) {
+            // this lane's slice of B for the step: issued first so that it is in flight during the staging
+            uint32_t aw[4] = {0u, 0u, 0u, 0u};
+            if constexpr (DTAB == DT_BF16) {
+                const RANDES_GLOBAL uint16_t *Bp = (const RANDES_GLOBAL uint16_t *)S.B;
+                const int32_t kb = k0 + (int32_t)half * 8;
+                if (row_ok && kb < rank) {
+                    if (b_vec_ok) {
+                        const u32x4 q = *(const RANDES_GLOBAL u32x4 *)(Bp + (int64_t)my_row * rank + kb);
+                        aw[0] = q.x; aw[1] = q.y; aw[2] = q.z; aw[3] = q.w;
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 8; ++j)
+                            if (kb + j < rank) aw[j >> 1] |= (uint32_t)Bp[(int64_t)my_row * rank + kb + j] << (16 * (j & 1));
+                    }
+                }
+            }
+            if (stage_now) {
             __syncthreads();   // the slab of the previous step is consumed; sbits are visible
             // ---- stage A[k0 .. k0+15][col0 .. col0+511], sign-flipped ----
             if constexpr (DTAB == DT_BF16) {
@@ -133,22 +162,10 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
                 }
             }
             __syncthreads();
+            }
             // ---- multiply ----
             if constexpr (DTAB == DT_BF16) {
                 const uint16_t *As = (const uint16_t *)smem;
-                const RANDES_GLOBAL uint16_t *Bp = (const RANDES_GLOBAL uint16_t *)S.B;
-                const int32_t kb = k0 + (int32_t)half * 8;
-                uint32_t aw[4] = {0u, 0u, 0u, 0u};
-                if (row_ok && kb < rank) {
-                    if (b_vec_ok) {
-                        const u32x4 q = *(const RANDES_GLOBAL u32x4 *)(Bp + (int64_t)my_row * rank + kb);
-                        aw[0] = q.x; aw[1] = q.y; aw[2] = q.z; aw[3] = q.w;
-                    } else {
-#pragma unroll
-                        for (int j = 0; j < 8; ++j)
-                            if (kb + j < rank) aw[j >> 1] |= (uint32_t)Bp[(int64_t)my_row * rank + kb + j] << (16 * (j & 1));
-                    }
-                }
                 u32x4 aq; aq.x = aw[0]; aq.y = aw[1]; aq.z = aw[2]; aq.w = aw[3];
                 const bf16x8 av = __builtin_bit_cast(bf16x8, aq);
 #pragma unroll
@@ -160,7 +177,10 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
                     bq.y = (uint32_t)col[2 * AS_STRIDE] | ((uint32_t)col[3 * AS_STRIDE] << 16);
                     bq.z = (uint32_t)col[4 * AS_STRIDE] | ((uint32_t)col[5 * AS_STRIDE] << 16);
                     bq.w = (uint32_t)col[6 * AS_STRIDE] | ((uint32_t)col[7 * AS_STRIDE] << 16);
-                    acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8, bq), acc[b], 0, 0, 0);
+                    if constexpr (DTO == DT_BF16)
+                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bq), av, acc[b], 0, 0, 0);
+                    else
+                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8, bq), acc[b], 0, 0, 0);
                 }
             } else {
                 const float *As = (const float *)smem;
@@ -173,7 +193,10 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
                         const uint32_t c = wave * 128u + (uint32_t)b * 32u + l32;
-                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, As[kk * AS_STRIDE + c], acc[b], 0, 0, 0);
+                        if constexpr (DTO == DT_BF16)
+                            acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(As[kk * AS_STRIDE + c], a, acc[b], 0, 0, 0);
+                        else
+                            acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, As[kk * AS_STRIDE + c], acc[b], 0, 0, 0);
                     }
                 }
             }
@@ -194,16 +217,20 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
             }
         }
     } else {
-        __syncthreads();   // everyone is done reading the A slab: reuse the LDS for the output
-        uint16_t *stg = (uint16_t *)smem + wave * (LORA_TILE_M * ST_STRIDE);
+        // each wave stages and drains its own region: ordering inside one wave is all that is needed
+        uint16_t *stg = (uint16_t *)sstage + wave * (LORA_TILE_M * ST_STRIDE);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave's reads of the previous block are done
+        // transposed product: this lane holds output row l32, columns b*32 + 8*g + 4*half + (0..3)
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int r = 8 * (v / 4) + 4 * (int)half + (v % 4);
-                stg[r * ST_STRIDE + b * 32 + (int)l32] = (uint16_t)bf16_rne(scale * acc[b][v]);
+            for (int g = 0; g < 4; ++g) {
+                u32x2 q;
+                q.x = bf16_rne(scale * acc[b][4 * g + 0]) | (bf16_rne(scale * acc[b][4 * g + 1]) << 16);
+                q.y = bf16_rne(scale * acc[b][4 * g + 2]) | (bf16_rne(scale * acc[b][4 * g + 3]) << 16);
+                *(u32x2 *)(stg + (int)l32 * ST_STRIDE + b * 32 + 8 * g + 4 * (int)half) = q;
             }
-        __syncthreads();
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the wave's writes have landed before any lane reads
         RANDES_GLOBAL uint16_t *out = (RANDES_GLOBAL uint16_t *)it.out;
         const bool o_vec_ok = (cols % 8 == 0) && (((uintptr_t)it.out & 15u) == 0);
         const int c8 = (int)(lane & 15u) * 8;
@@ -224,21 +251,22 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
             }
         }
     }
+  }   // row blocks
 }
 
-hipError_t launch_lora(const LoraItem *items_dev, int32_t n_items, const LoraSeg *segs_dev, uint32_t n_tiles,
-                       int32_t rank, float scale, int dt_ab, int dt_out, hipStream_t s)
+hipError_t launch_lora(const LoraItem *items_dev, int32_t n_items, const LoraSeg *segs_dev, const uint32_t *coarse_dev,
+                       uint32_t n_tiles, int32_t rank, float scale, int dt_ab, int dt_out, hipStream_t s)
 {
     if (n_tiles == 0) return hipSuccess;
     const dim3 grid(n_tiles), block(WG);
     if (dt_ab == DT_BF16 && dt_out == DT_BF16)
-        hipLaunchKernelGGL((lora_kernel<DT_BF16, DT_BF16>), grid, block, 0, s, items_dev, n_items, segs_dev, rank, scale);
+        hipLaunchKernelGGL((lora_kernel<DT_BF16, DT_BF16>), grid, block, 0, s, items_dev, n_items, segs_dev, coarse_dev, rank, scale);
     else if (dt_ab == DT_BF16)
-        hipLaunchKernelGGL((lora_kernel<DT_BF16, DT_F32>), grid, block, 0, s, items_dev, n_items, segs_dev, rank, scale);
+        hipLaunchKernelGGL((lora_kernel<DT_BF16, DT_F32>), grid, block, 0, s, items_dev, n_items, segs_dev, coarse_dev, rank, scale);
     else if (dt_out == DT_BF16)
-        hipLaunchKernelGGL((lora_kernel<DT_F32, DT_BF16>), grid, block, 0, s, items_dev, n_items, segs_dev, rank, scale);
+        hipLaunchKernelGGL((lora_kernel<DT_F32, DT_BF16>), grid, block, 0, s, items_dev, n_items, segs_dev, coarse_dev, rank, scale);
     else
-        hipLaunchKernelGGL((lora_kernel<DT_F32, DT_F32>), grid, block, 0, s, items_dev, n_items, segs_dev, rank, scale);
+        hipLaunchKernelGGL((lora_kernel<DT_F32, DT_F32>), grid, block, 0, s, items_dev, n_items, segs_dev, coarse_dev, rank, scale);
     return hipGetLastError();
 }
 

@@ -395,3 +395,37 @@ def test_delta_stats(dt):
     # reproducible bit for bit
     again = rb.delta_stats(flagged, gf, 42, gf, 43).cpu().numpy()
     assert np.array_equal(again.view(np.uint64), c_diff.view(np.uint64))
+
+
+def test_factor_space_lora_superposition():
+    # The paper superposes "LoRA weight vectors": the factors A and B themselves can be the layers of
+    # the same merge / retrieve kernels (storage stays at adapter size); the dense update is then
+    # materialised from the retrieved factors.  A factors form one group, B factors another.
+    n_mod, rank, K = 6, 16, 3
+    stack = []
+    for _ in range(n_mod):
+        stack.append(Layer(rank, 768, 0, SRSF))   # A: rank x cols
+        stack.append(Layer(768, rank, 1, SRSF))   # B: rows x rank
+    layers = layers_of(stack)
+    seeds = [42, 43, 44]
+    g = torch.Generator().manual_seed(7)
+    factors = [[(torch.randn(l.rows, l.cols, generator=g) * 0.01).to(torch.bfloat16) for l in stack] for _ in range(K)]
+    zero = [torch.zeros(l.rows, l.cols, dtype=torch.bfloat16) for l in stack]
+    gm = rb.merge(layers, [to_gpu(f) for f in factors], seeds)
+    om = oracle.merge(layers, [np_lists(f) for f in factors], seeds, 1, 1)
+    for l in range(len(stack)):
+        compare(gm[l], om[l], "factor merge %d" % l)
+    got = rb.retrieve(layers, gm, to_gpu(zero), seeds[1], 1.0)
+    want = oracle.retrieve(layers, om, np_lists(zero), seeds[1], 1.0, 1, 1, 1)
+    for l in range(len(stack)):
+        compare(got[l], want[l], "factor retrieve %d" % l)
+    # dense update of module 2 from the retrieved factors, against the float64 product of the same factors
+    A_hat, B_hat = got[4], got[5]
+    dense = rb.lora_materialize(B_hat, A_hat, 1.0, out_dtype=torch.float32).cpu().numpy().astype(np.float64)
+    ref, mag = oracle.lora(to_np(B_hat), to_np(A_hat), 1.0, 1)
+    assert (np.abs(dense - ref) <= rank * 2.0 ** -24 * mag + 2.0 ** -23 * np.abs(ref) + 1e-45).all()
+    # a single model comes back exactly
+    g1 = rb.merge(layers, [to_gpu(factors[0])], [seeds[0]])
+    back = rb.retrieve(layers, g1, to_gpu(zero), seeds[0], 1.0)
+    for l in range(len(stack)):
+        assert torch.equal(back[l].cpu().view(torch.int16), factors[0][l].view(torch.int16))
