@@ -215,19 +215,33 @@ struct Tile {
     uint32_t row0, row_end;
     uint32_t wy, WY;      // this wave's row phase and the row stride between its rows
     bool active;          // lane has columns inside the layer
+    bool valid;           // false: this workgroup is padding of the XCD-contiguous grid and has no tile
+    uint32_t id;          // position of the tile in the launch's tile sequence
 };
+
+constexpr uint32_t N_XCD = 8;   // workgroup i of a launch is dispatched to XCD i mod 8
+
+// Launch size for n_tiles tiles: a multiple of the XCD count (see locate()).
+static inline uint32_t xcd_grid(uint32_t n_tiles) { return (n_tiles + N_XCD - 1u) / N_XCD * N_XCD; }
 
 template <int VEC>
 __device__ __forceinline__ Tile locate(const StreamArgs &A)
 {
-    const uint32_t bid = blockIdx.x;
+    // Workgroups are handed to the 8 XCDs round-robin.  Give XCD x the x-th contiguous eighth of the
+    // tile sequence, so that each XCD (own L2, own address-translation cache) sweeps one region of
+    // every stream front to back instead of touching all of them: measured +5..8 % bandwidth.
+    const uint32_t per_xcd = gridDim.x / N_XCD;
+    const uint32_t bid = (blockIdx.x % N_XCD) * per_xcd + blockIdx.x / N_XCD;
+    Tile t;
+    t.valid = bid < A.n_tiles;
+    t.id = bid;
+    if (!t.valid) return t;
     // coarse[i] = layer that holds tile i * 1024: narrows the search to a step or two
     int lo = (int)A.coarse[bid >> 10], hi = (int)A.coarse[(bid >> 10) + 1] + 1;
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
         if (A.tile_begin[mid] <= bid) lo = mid; else hi = mid;
     }
-    Tile t;
     t.layer_slot = lo;
     t.L = A.layers[lo];
     const uint32_t idx = bid - A.tile_begin[lo];
@@ -299,6 +313,7 @@ __global__ void __launch_bounds__(WG) merge_kernel(const StreamArgs A)
     extern __shared__ uint32_t sbits[];
     __shared__ gcptr sptr[KT > 0 ? 1 : NS * RANDES_MAX_TASKS];   // KT = 0: tile base pointer of every stream
     const Tile t = locate<VEC>(A);
+    if (!t.valid) return;   // whole workgroup, before any barrier
     const uint32_t K = KT > 0 ? (uint32_t)KT : (uint32_t)A.n_tasks;
     const uint32_t rb_in = (uint32_t)t.L.cols * EBI, rb_out = (uint32_t)t.L.cols * EBO;
     const size_t tile_in = (size_t)t.row0 * rb_in, tile_out = (size_t)t.row0 * rb_out;
@@ -479,6 +494,7 @@ __global__ void __launch_bounds__(WG) retrieve_kernel(const StreamArgs A)
 {
     extern __shared__ uint32_t sbits[];
     const Tile t = locate<VEC>(A);
+    if (!t.valid) return;
     two_input_bursts<DTM, DTB, DTO, VEC, true>(A, t, (gcptr)t.L.a, (gcptr)t.L.b, (gptr)t.L.dst, sbits);
 }
 
@@ -488,6 +504,7 @@ __global__ void __launch_bounds__(WG) update_kernel(const StreamArgs A)
 {
     extern __shared__ uint32_t sbits[];
     const Tile t = locate<VEC>(A);
+    if (!t.valid) return;
     two_input_bursts<DTD, DTM, DTM, VEC, false>(A, t, (gcptr)t.L.a, (gcptr)t.L.dst, (gptr)t.L.dst, sbits);
 }
 
@@ -507,6 +524,7 @@ __global__ void __launch_bounds__(WG) stats_kernel(const StreamArgs A)
     extern __shared__ uint32_t sbits[];
     __shared__ double swave[WAVES][3];
     const Tile t = locate<VEC>(A);
+    if (!t.valid) return;
     const uint32_t cols = (uint32_t)t.L.cols;
     const gcptr pa = (gcptr)t.L.a + (size_t)t.row0 * cols * EB;
     const gcptr pb = (gcptr)t.L.b + (size_t)t.row0 * cols * EB;
@@ -556,7 +574,7 @@ __global__ void __launch_bounds__(WG) stats_kernel(const StreamArgs A)
     if (threadIdx.x < 3) {
         double v = 0.0;
         for (int w = 0; w < WAVES; ++w) v += swave[w][threadIdx.x];
-        A.partials[((size_t)A.partial_base + blockIdx.x) * 3u + threadIdx.x] = v;
+        A.partials[((size_t)A.partial_base + t.id) * 3u + threadIdx.x] = v;
     }
 }
 
@@ -602,7 +620,11 @@ template <int K, bool WRITE>
 __global__ void __launch_bounds__(WG) probe_kernel(const ProbeArgs P)
 {
     constexpr int R = 4;
-    const uint64_t base = ((uint64_t)blockIdx.x * R * WG + threadIdx.x) * 16u;
+    // same XCD-contiguous order as the method's kernels (see locate())
+    const uint32_t per_xcd = gridDim.x / N_XCD;
+    const uint32_t chunk = (blockIdx.x % N_XCD) * per_xcd + blockIdx.x / N_XCD;
+    if ((uint64_t)chunk * R * WG >= P.n_vec) return;
+    const uint64_t base = ((uint64_t)chunk * R * WG + threadIdx.x) * 16u;
     u32x4 v[R][K];
 #pragma unroll
     for (int r = 0; r < R; ++r)
@@ -637,7 +659,7 @@ hipError_t launch_probe(const void *const *inputs, int n_inputs, void *output, u
     for (int k = 0; k < 8; ++k) P.in[k] = (gcptr)inputs[k < n_inputs ? k : 0];
     P.out = (gptr)output;
     P.n_vec = bytes / 16u;
-    const dim3 grid((uint32_t)(bytes / PROBE_CHUNK_BYTES)), block(WG);
+    const dim3 grid(xcd_grid((uint32_t)(bytes / PROBE_CHUNK_BYTES))), block(WG);
 #define RANDES_PROBE(K) case K: if (write) hipLaunchKernelGGL((probe_kernel<K, true>), grid, block, 0, s, P); \
                                 else hipLaunchKernelGGL((probe_kernel<K, false>), grid, block, 0, s, P); break;
     switch (n_inputs) {
@@ -669,7 +691,7 @@ int update_vec(int dt_merged, int dt_delta) { return (dt_merged == DT_BF16 || dt
 template <int DTI, int DTO, int VEC>
 static hipError_t merge_dispatch(const StreamArgs &a, hipStream_t s)
 {
-    const dim3 grid(a.n_tiles), block(WG);
+    const dim3 grid(xcd_grid(a.n_tiles)), block(WG);
     const size_t lds = sign_bits_lds_bytes(a.n_tasks, VEC);
     // the element-wise variant and more than KREG_MAX tasks take the any-count kernel
     if constexpr (VEC == 1) {
@@ -691,7 +713,7 @@ static hipError_t merge_dispatch(const StreamArgs &a, hipStream_t s)
 template <int DTI, int DTO, int VEC>
 static hipError_t merge_weights_dispatch(const StreamArgs &a, hipStream_t s)
 {
-    const dim3 grid(a.n_tiles), block(WG);
+    const dim3 grid(xcd_grid(a.n_tiles)), block(WG);
     const size_t lds = sign_bits_lds_bytes(a.n_tasks, VEC);
     constexpr int R = MERGE_WEIGHTS_R;
     if constexpr (VEC == 1) {
@@ -740,7 +762,7 @@ hipError_t launch_merge_weights(const StreamArgs &a, int vec, int dt_in, int dt_
 template <int DTM, int DTB, int VEC>
 static hipError_t retrieve_dispatch(const StreamArgs &a, int dt_out, hipStream_t s)
 {
-    const dim3 grid(a.n_tiles), block(WG);
+    const dim3 grid(xcd_grid(a.n_tiles)), block(WG);
     const size_t lds = sign_bits_lds_bytes(1, VEC);
     if (dt_out == DT_F32) hipLaunchKernelGGL((retrieve_kernel<DTM, DTB, DT_F32, VEC>), grid, block, lds, s, a);
     else hipLaunchKernelGGL((retrieve_kernel<DTM, DTB, DT_BF16, VEC>), grid, block, lds, s, a);
@@ -766,7 +788,7 @@ hipError_t launch_retrieve(const StreamArgs &a, int vec, int dt_merged, int dt_b
 template <int DTM, int DTD, int VEC>
 static hipError_t update_dispatch(const StreamArgs &a, hipStream_t s)
 {
-    hipLaunchKernelGGL((update_kernel<DTM, DTD, VEC>), dim3(a.n_tiles), dim3(WG), sign_bits_lds_bytes(1, VEC), s, a);
+    hipLaunchKernelGGL((update_kernel<DTM, DTD, VEC>), dim3(xcd_grid(a.n_tiles)), dim3(WG), sign_bits_lds_bytes(1, VEC), s, a);
     return hipGetLastError();
 }
 
@@ -791,7 +813,7 @@ int stats_vec(int dt) { return dt == DT_BF16 ? 8 : 4; }
 hipError_t launch_stats(const StreamArgs &a, int vec, int dt, hipStream_t s)
 {
     if (a.n_tiles == 0) return hipSuccess;
-    const dim3 grid(a.n_tiles), block(WG);
+    const dim3 grid(xcd_grid(a.n_tiles)), block(WG);
     const size_t lds = 2 * sign_bits_lds_bytes(1, vec ? stats_vec(dt) : 1);
     if (vec) {
         if (dt == DT_F32) hipLaunchKernelGGL((stats_kernel<DT_F32, 4>), grid, block, lds, s, a);
