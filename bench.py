@@ -28,6 +28,12 @@ from paper_2505_11204_amd import workloads as wl        # noqa: E402
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same counters
+# read for a plain copy of known size (FETCH_SIZE x 2.0000, WRITE_SIZE x 1.0000); see
+# profiles/llama_7b_bf16_k8_merge_retrieve.txt.  Valid for the kernels as committed with that profile;
+# set to None whenever a kernel changes until the counters are taken again.
+MEASURED_TRAFFIC_BYTES = {"llama_7b": {"retrieve": 40.429e9, "merge": 121.285e9}}
+
 WORKLOADS = {
     # name: (stack fn, storage dtype, K, requests, delta std, per-task scales?)
     "llama_7b": (wl.llama_7b, "bf16", 8, 64, 5e-4, False),
@@ -244,9 +250,11 @@ def main():
                          "pct_of_hbm_peak": 100.0 * retr_gbs / HBM_PEAK_GBS},
         },
         "roofline": {"kernel": "retrieve_kernel", "bound": "hbm", "achieved": retr_gbs, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": retr_gbs / HBM_PEAK_GBS, "traffic": None},
+                     "unit": "GB/s", "frac": retr_gbs / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload, {}).get("retrieve")},
         "roofline_merge": {"kernel": "merge_kernel", "bound": "hbm", "achieved": merge_gbs, "peak": HBM_PEAK_GBS,
-                           "unit": "GB/s", "frac": merge_gbs / HBM_PEAK_GBS, "traffic": None},
+                           "unit": "GB/s", "frac": merge_gbs / HBM_PEAK_GBS,
+                           "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload, {}).get("merge")},
     }
     if ceil is not None:
         result["config"]["plain_streaming_ceilings"] = ceil
