@@ -86,12 +86,12 @@ uint64_t plan_layer_geometry(LayerDev *d, int vec, int rows_per_wave, int max_wx
     d->wx = 1u << best_shift;
     const uint64_t cw = (uint64_t)(64 * vec) << best_shift;
     d->n_cb = (uint32_t)((cols + cw - 1) / cw);
-    // in-tile byte offsets are 32-bit: (tile_rows + rows in flight) * cols * 4 must stay below 2^31
+    // in-tile byte offsets are 32-bit: tile_rows * cols * 4 (the widest element) must stay below 2^32
     const uint64_t row_bytes = cols * 4;
-    const uint64_t max_rows = ((uint64_t)1 << 31) / row_bytes;
-    if (max_rows < 17) return 0;
+    const uint64_t max_rows = (((uint64_t)1 << 32) - 1) / row_bytes;
+    if (max_rows < 1) return 0;
     uint64_t tr = (uint64_t)rows_per_wave << (2 - best_shift);   // 4 waves: 4 / wx of them stacked along the rows
-    if (tr > max_rows - 16) tr = max_rows - 16;
+    if (tr > max_rows) tr = max_rows;
     if (tr > rows) tr = rows;
     if (tr < 1) tr = 1;
     d->tile_rows = (uint32_t)tr;

@@ -429,3 +429,18 @@ def test_factor_space_lora_superposition():
     back = rb.retrieve(layers, g1, to_gpu(zero), seeds[0], 1.0)
     for l in range(len(stack)):
         assert torch.equal(back[l].cpu().view(torch.int16), factors[0][l].view(torch.int16))
+
+
+@pytest.mark.parametrize("rows,cols", [(3, 5_000_008), (1, 33_554_432), (300_000, 8), (2, 40_000_001), (70_001, 24)])
+def test_extreme_shapes(rows, cols):
+    # very wide (many generator blocks, offsets near the 32-bit in-tile limit) and very tall, thin layers
+    stack = [Layer(rows, cols, -1, FLIP)]
+    layers = layers_of(stack)
+    base, deltas = cpu_inputs(stack, 2, "bf16")
+    seeds = [5, 6]
+    m = rb.merge(layers, [to_gpu(d) for d in deltas], seeds)
+    om = oracle.merge(layers, [np_lists(d) for d in deltas], seeds, 1, 1, n_threads=8)
+    compare(m[0], om[0], "extreme merge")
+    out = rb.retrieve(layers, m, to_gpu(base), 6, 0.5)
+    oo = oracle.retrieve(layers, om, np_lists(base), 6, 0.5, 1, 1, 1, n_threads=8)
+    compare(out[0], oo[0], "extreme retrieve")
