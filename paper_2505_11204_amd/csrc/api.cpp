@@ -372,7 +372,8 @@ int randes_retrieve(const randes_layer *layers, int32_t n_layers,
             d.layer_id = (uint32_t)l;
             d.flip = (layers[l].flags & RANDES_FLIP) ? 1u : 0u;
             const bool vector_ok = (layers[l].cols % vec) == 0 && aligned16(d.dst) && aligned16(d.a) && aligned16(d.b);
-            if ((rc = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(g_retrieve_rows, two_input_burst_rows())))) return rc;
+            const int burst = two_input_burst_rows(merged_dtype, base_dtype, vector_ok ? vec : 1);
+            if ((rc = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(g_retrieve_rows, burst)))) return rc;
         }
         CachedPlan fresh;
         fresh.key = key;
@@ -440,7 +441,8 @@ int randes_update(const randes_layer *layers, int32_t n_layers,
             d.layer_id = (uint32_t)l;
             d.flip = (layers[l].flags & RANDES_FLIP) ? 1u : 0u;
             const bool vector_ok = (layers[l].cols % vec) == 0 && aligned16(d.dst) && aligned16(d.a);
-            if ((rc = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(g_retrieve_rows, two_input_burst_rows())))) return rc;
+            const int burst = two_input_burst_rows(delta_dtype, merged_dtype, vector_ok ? vec : 1);
+            if ((rc = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(g_retrieve_rows, burst)))) return rc;
         }
         CachedPlan fresh;
         fresh.key = key;
@@ -500,7 +502,8 @@ int randes_delta_stats(const randes_layer *layers, int32_t n_layers,
             d.layer_id = (uint32_t)l;
             d.flip = (layers[l].flags & RANDES_FLIP) ? 1u : 0u;
             const bool vector_ok = (layers[l].cols % vec) == 0 && aligned16(d.a) && aligned16(d.b);
-            if ((rc = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(g_retrieve_rows, two_input_burst_rows())))) return rc;
+            const int burst = two_input_burst_rows(dtype, dtype, vector_ok ? vec : 1);
+            if ((rc = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(g_retrieve_rows, burst)))) return rc;
         }
         hp.extra_bytes = ((size_t)hp.vec.n_tiles + hp.scl.n_tiles) * 3 * sizeof(double);
         CachedPlan fresh;

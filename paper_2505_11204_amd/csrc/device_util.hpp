@@ -20,15 +20,11 @@ constexpr int KREG_MAX = 8;      // merge: up to this many tasks keep their mask
 #ifndef RANDES_MERGE_R
 #define RANDES_MERGE_R 4
 #endif
-#ifndef RANDES_TWO_INPUT_R
-#define RANDES_TWO_INPUT_R 8
-#endif
 #ifndef RANDES_STORE_AT_END
 #define RANDES_STORE_AT_END 1
 #endif
 constexpr bool STORE_AT_END = RANDES_STORE_AT_END != 0;   // hold a burst's results until all of them exist
 constexpr int MERGE_R = RANDES_MERGE_R;          // merge: rows a wave loads before it stores (one burst)
-constexpr int TWO_INPUT_R = RANDES_TWO_INPUT_R;  // retrieve / update: the same
 constexpr int MERGE_WEIGHTS_R = MERGE_R / 2 > 0 ? MERGE_R / 2 : 1;   // merge from weights: two streams per task
 
 __device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }

@@ -442,7 +442,7 @@ __device__ __forceinline__ void two_input_bursts(const StreamArgs &A, const Tile
 {
     constexpr uint32_t EBX = (DTX == DT_F32) ? 4 : 2, EBY = (DTY == DT_F32) ? 4 : 2, EBO = (DTO == DT_F32) ? 4 : 2;
     constexpr int NWX = NumWords<DTX, VEC>::value, NWY = NumWords<DTY, VEC>::value, NWO = OutWords<DTO, VEC>::value;
-    constexpr int R = TWO_INPUT_R;
+    constexpr int R = two_input_rows(NWX, NWY);
     const uint32_t cols = (uint32_t)t.L.cols;
     px += (size_t)t.row0 * cols * EBX;
     py += (size_t)t.row0 * cols * EBY;
@@ -520,7 +520,7 @@ __global__ void __launch_bounds__(WG) stats_kernel(const StreamArgs A)
 {
     constexpr uint32_t EB = (DT == DT_F32) ? 4 : 2;
     constexpr int NW = NumWords<DT, VEC>::value;
-    constexpr int R = TWO_INPUT_R;
+    constexpr int R = two_input_rows(NW, NW);
     extern __shared__ uint32_t sbits[];
     __shared__ double swave[WAVES][3];
     const Tile t = locate<VEC>(A);
@@ -684,7 +684,6 @@ static size_t sign_bits_lds_bytes(int n_tasks, int vec)
 int merge_vec(int dt_in) { return dt_in == DT_BF16 ? 8 : 4; }
 int merge_burst_rows() { return MERGE_R; }
 int merge_weights_burst_rows() { return MERGE_WEIGHTS_R; }
-int two_input_burst_rows() { return TWO_INPUT_R; }
 int retrieve_vec(int dt_merged, int dt_base) { return (dt_merged == DT_BF16 || dt_base == DT_BF16) ? 8 : 4; }
 int update_vec(int dt_merged, int dt_delta) { return (dt_merged == DT_BF16 || dt_delta == DT_BF16) ? 8 : 4; }
 

@@ -50,7 +50,19 @@ int update_vec(int dt_merged, int dt_delta);
 int stats_vec(int dt);
 int merge_burst_rows();
 int merge_weights_burst_rows();
-int two_input_burst_rows();
+// Two-input kernels (retrieve, update, stats): rows per burst so that about 32 sixteen-byte loads are
+// in flight per lane: 16 rows when both streams fit 16 bytes per lane, fewer when a stream is wider.
+// words_x / words_y = 32-bit words per lane and row of the two streams.
+constexpr int two_input_rows(int words_x, int words_y)
+{
+    const int w = words_x + words_y;
+    return w <= 8 ? 16 : (w <= 16 ? 8 : 4);
+}
+constexpr int stream_words(int dt, int vec) { return dt == DT_F32 ? vec : (vec == 1 ? 1 : vec / 2); }
+inline int two_input_burst_rows(int dt_x, int dt_y, int vec)
+{
+    return two_input_rows(stream_words(dt_x, vec), stream_words(dt_y, vec));
+}
 
 // Plain streaming probe: out = sum of n_inputs streams (write != 0) or loads only (write == 0).
 // bytes per stream must be a multiple of PROBE_CHUNK_BYTES.

@@ -74,10 +74,11 @@ int build_source_table(const randes_layer *layers, int32_t n_layers, uint64_t se
 uint64_t plan_layer_geometry(LayerDev *d, int vec, int rows_per_wave, int max_wx_shift)
 {
     const uint64_t cols = (uint64_t)d->cols, rows = (uint64_t)d->rows;
-    // waves along the columns: the widest arrangement that wastes the fewest lanes
+    // waves along the columns: the arrangement that wastes the fewest lanes; among equals the
+    // narrowest (4 waves stacked along the rows measured 1-2 % faster than 4 side by side)
     uint32_t best_shift = 0;
     uint64_t best_waste = ~0ull;
-    for (int sh = max_wx_shift; sh >= 0; --sh) {
+    for (int sh = 0; sh <= max_wx_shift; ++sh) {
         const uint64_t cw = (uint64_t)(64 * vec) << sh;
         const uint64_t waste = (cols + cw - 1) / cw * cw - cols;
         if (waste < best_waste) { best_waste = waste; best_shift = (uint32_t)sh; }
