@@ -31,7 +31,19 @@
 namespace randes {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// Two binary32 values -> one dword of two bf16, with the hardware's packed round-to-nearest-even
+// conversion (v_cvt_pk_bf16_f32).  Used only here, where results are checked to a tolerance; the
+// streaming kernels use the integer sequence whose every bit the oracle reproduces.
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    f32x2 v;
+    v.x = lo; v.y = hi;
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
 
 constexpr int KCH = 16;                 // rank slice per staging step
 constexpr int AS_STRIDE = LORA_TILE_N + 8;   // elements per staged depth row (keeps rows 16-byte aligned)
@@ -64,6 +76,9 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
     const int32_t col0 = (int32_t)tx * LORA_TILE_N;
     const int32_t rows = it.rows, cols = it.cols;
     const bool reuse_slab = (it.n_seg == 1) && (rank <= KCH);   // one staging serves every row block
+    u32x4 frag[4];   // bf16 factors: this lane's right-operand fragments of the four 32-column blocks
+#pragma unroll
+    for (int b = 0; b < 4; ++b) frag[b] = u32x4{0u, 0u, 0u, 0u};
 
   for (int rt = 0; rt < LORA_ROW_TILES; ++rt) {
     const int32_t row0 = ((int32_t)ty * LORA_ROW_TILES + rt) * LORA_TILE_M;
@@ -170,13 +185,15 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
                 const bf16x8 av = __builtin_bit_cast(bf16x8, aq);
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
-                    const uint32_t c = wave * 128u + (uint32_t)b * 32u + l32;
-                    const uint16_t *col = As + (half * 8u) * AS_STRIDE + c;
-                    u32x4 bq;
-                    bq.x = (uint32_t)col[0 * AS_STRIDE] | ((uint32_t)col[1 * AS_STRIDE] << 16);
-                    bq.y = (uint32_t)col[2 * AS_STRIDE] | ((uint32_t)col[3 * AS_STRIDE] << 16);
-                    bq.z = (uint32_t)col[4 * AS_STRIDE] | ((uint32_t)col[5 * AS_STRIDE] << 16);
-                    bq.w = (uint32_t)col[6 * AS_STRIDE] | ((uint32_t)col[7 * AS_STRIDE] << 16);
+                    if (stage_now) {   // with a reused slab the gathered fragments serve every row block
+                        const uint32_t c = wave * 128u + (uint32_t)b * 32u + l32;
+                        const uint16_t *col = As + (half * 8u) * AS_STRIDE + c;
+                        frag[b].x = (uint32_t)col[0 * AS_STRIDE] | ((uint32_t)col[1 * AS_STRIDE] << 16);
+                        frag[b].y = (uint32_t)col[2 * AS_STRIDE] | ((uint32_t)col[3 * AS_STRIDE] << 16);
+                        frag[b].z = (uint32_t)col[4 * AS_STRIDE] | ((uint32_t)col[5 * AS_STRIDE] << 16);
+                        frag[b].w = (uint32_t)col[6 * AS_STRIDE] | ((uint32_t)col[7 * AS_STRIDE] << 16);
+                    }
+                    const u32x4 bq = frag[b];
                     if constexpr (DTO == DT_BF16)
                         acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bq), av, acc[b], 0, 0, 0);
                     else
@@ -226,8 +243,8 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 u32x2 q;
-                q.x = bf16_rne(scale * acc[b][4 * g + 0]) | (bf16_rne(scale * acc[b][4 * g + 1]) << 16);
-                q.y = bf16_rne(scale * acc[b][4 * g + 2]) | (bf16_rne(scale * acc[b][4 * g + 3]) << 16);
+                q.x = pack_bf16x2(scale * acc[b][4 * g + 0], scale * acc[b][4 * g + 1]);
+                q.y = pack_bf16x2(scale * acc[b][4 * g + 2], scale * acc[b][4 * g + 3]);
                 *(u32x2 *)(stg + (int)l32 * ST_STRIDE + b * 32 + 8 * g + 4 * (int)half) = q;
             }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the wave's writes have landed before any lane reads
