@@ -1,14 +1,14 @@
-// gfx950 kernels of the RanDeS hot path: streaming merge (compress), fused
-// retrieve, in-place hot-swap update, sign-mask dump, and the MFMA LoRA
-// materialiser.  Wavefronts are 64 lanes; a workgroup is 4 waves.
+// gfx950 streaming kernels of the RanDeS hot path: merge (compress, from deltas or straight from
+// weights), fused retrieve, in-place hot-swap update, the Sec. 3 diagnostics, the sign-mask dump,
+// and a plain bandwidth probe.  Wavefronts are 64 lanes; a workgroup is 4 waves.
 //
-// Streaming kernels: one workgroup owns a tile = (slot layer, chunk of rows,
-// block of columns).  A lane owns VEC adjacent columns and walks down the rows
-// of the tile, so the sign bits of its columns (Sec. 4.4: D is diagonal over the
-// columns) are generated once per tile and kept in registers as XOR masks; the
-// weight stream itself goes HBM -> registers -> HBM with 16-byte accesses and
-// never touches LDS.  The shuffle (Sec. 4.3) costs nothing here: it is already
-// folded into the pointer tables.
+// One workgroup owns a tile = (slot layer, a few rows, a block of columns).  A lane owns VEC
+// adjacent columns (one 16-byte access per row and stream).  Each wave does ONE burst: it issues
+// every load of its rows back to back, the workgroup produces the tile's sign bits (Sec. 4.4: D
+// is diagonal over the columns, so bits depend on the column only) into LDS while those loads are
+// in flight, then the wave does its arithmetic and issues all its stores last.  The weight stream
+// goes HBM -> registers -> HBM and never touches LDS; the sign flip is an XOR on the loaded words.
+// The shuffle (Sec. 4.3) costs nothing here: it is already folded into the pointer tables.
 #include <hip/hip_runtime.h>
 
 #include "device_util.hpp"
@@ -68,38 +68,6 @@ __device__ __forceinline__ uint32_t lane_sign_bits(uint32_t key_lo, uint32_t key
     const uint32_t sel = (col >> 5) & 3u;
     const uint32_t word = sel == 0 ? o.w[0] : sel == 1 ? o.w[1] : sel == 2 ? o.w[2] : o.w[3];
     return (word >> (col & 31u)) & ((VEC == 32) ? 0xffffffffu : ((1u << VEC) - 1u));
-}
-
-// Sign bits -> XOR masks laid over the raw dwords of a VEC-element load.
-template <int DT, int VEC>
-__device__ __forceinline__ void packed_sign_masks(uint32_t bits, uint32_t (&pm)[NumWords<DT, VEC>::value])
-{
-    if constexpr (DT == DT_F32) {
-#pragma unroll
-        for (int j = 0; j < VEC; ++j) pm[j] = ((bits >> j) & 1u) << 31;
-    } else if constexpr (VEC == 1) {
-        pm[0] = (bits & 1u) << 15;
-    } else {
-#pragma unroll
-        for (int j = 0; j < VEC / 2; ++j)
-            pm[j] = (((bits >> (2 * j)) & 1u) << 15) | (((bits >> (2 * j + 1)) & 1u) << 31);
-    }
-}
-
-// acc[j] += (+/-) x[j] for the VEC elements of one task's load; the sign flip is
-// an XOR on the packed data, the addition is a plain binary32 add.
-template <int DT, int VEC>
-__device__ __forceinline__ void accumulate(const uint32_t (&raw)[NumWords<DT, VEC>::value],
-                                           const uint32_t (&pm)[NumWords<DT, VEC>::value], float (&acc)[VEC])
-{
-    constexpr int NW = NumWords<DT, VEC>::value;
-    uint32_t t[NW];
-#pragma unroll
-    for (int j = 0; j < NW; ++j) t[j] = raw[j] ^ pm[j];
-    float v[VEC];
-    widen<DT, VEC>(t, v);
-#pragma unroll
-    for (int j = 0; j < VEC; ++j) acc[j] = acc[j] + v[j];
 }
 
 // One register per task: this lane's sign bits arranged so that a shift and an AND give the XOR
