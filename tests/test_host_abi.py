@@ -103,6 +103,22 @@ def test_bad_arguments_are_error_codes_not_crashes(lib):
     assert lib.randes_lora_materialize(None, ptr, 4, 4, 2, ctypes.c_float(1.0), 0, ptr, 0, None) == EINVAL
     assert lib.randes_lora_materialize(ptr, ptr, 4, 4, 0, ctypes.c_float(1.0), 0, ptr, 0, None) == EINVAL
     assert lib.randes_update(one, 1, ptr, 0, None, 0, 1, 0, None) == EINVAL
+    # the fused front-ends, diagnostics and the probe
+    assert lib.randes_merge_weights(one, 1, ptr, None, 1, seeds, 0, ptr, 0, None) == EINVAL
+    assert lib.randes_merge_weights(one, 1, ptr, null, 1, seeds, 0, ptr, 0, None) == EINVAL
+    assert lib.randes_merge_weights(None, 1, ptr, ptr, 1, seeds, 0, ptr, 0, None) == EINVAL
+    assert lib.randes_delta_stats(one, 1, ptr, 1, ptr, 2, 0, None, None) == EINVAL
+    assert lib.randes_delta_stats(one, 1, null, 1, ptr, 2, 0, ptr, None) == EINVAL
+    assert lib.randes_delta_stats(one, 1, ptr, 1, ptr, 2, 9, ptr, None) == EINVAL
+    assert lib.randes_lora_merge(one, 1, ptr, ptr, 0, 1, seeds, ctypes.c_float(1.0), 0, ptr, 0, None) == EINVAL
+    assert lib.randes_lora_merge(one, 1, ptr, null, 4, 1, seeds, ctypes.c_float(1.0), 0, ptr, 0, None) == EINVAL
+    assert lib.randes_lora_merge(one, 1, ptr, ptr, 4, rb.MAX_TASKS + 1, seeds, ctypes.c_float(1.0), 0, ptr, 0, None) == ENOTSUP
+    assert lib.randes_lora_merge(one, 1, ptr, ptr, 4, 1, seeds, ctypes.c_float(float("nan")), 0, ptr, 0, None) == EINVAL
+    assert lib.randes_probe_stream(ptr, 0, ptr, 16384, 1, None) == EINVAL
+    assert lib.randes_probe_stream(ptr, 9, ptr, 16384, 1, None) == EINVAL
+    assert lib.randes_probe_stream(ptr, 1, ptr, 1000, 1, None) == EINVAL
+    unaligned = (ctypes.c_void_p * 1)(0x1004)
+    assert lib.randes_probe_stream(unaligned, 1, ptr, 16384, 1, None) == EINVAL
     assert lib.randes_set_tile_rows(-1, 0) == EINVAL
     assert lib.randes_set_tile_rows(0, 0) == 0
     assert lib.randes_set_tile_cols(3) == EINVAL
