@@ -26,7 +26,8 @@
  *    the default stream).  Calls do not synchronise; results are valid once
  *    the caller has synchronised the stream.  Buffers must stay alive until
  *    then.
- *  - 16-byte aligned layers whose cols is a multiple of 4 (f32) / 8 (bf16)
+ *  - Layer pointers must be aligned to their element size (else RANDES_EINVAL).
+ *    16-byte aligned layers whose cols is a multiple of 4 (f32) / 8 (bf16)
  *    take the vectorised kernels; anything else takes a slower element-wise
  *    kernel with identical results.
  */

@@ -36,6 +36,7 @@ int hip_fail(hipError_t e, const char *what)
 bool dtype_ok(int d) { return d == RANDES_F32 || d == RANDES_BF16; }
 size_t elem_bytes(int d) { return d == RANDES_F32 ? 4 : 2; }
 bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+bool elem_aligned(const void *p, int dtype) { return ((uintptr_t)p & (elem_bytes(dtype) - 1)) == 0; }
 
 int g_merge_rows = 0, g_retrieve_rows = 0;   // rows per wave per tile; 0 = the kernels' burst size
 int g_max_wx_shift = 2;   // widest tile: 4 waves side by side along the columns
@@ -214,12 +215,14 @@ int merge_impl(const randes_layer *layers, int32_t n_layers,
     if (n_tasks > RANDES_MAX_TASKS) return fail(RANDES_ENOTSUP, "n_tasks above RANDES_MAX_TASKS");
     if (!dtype_ok(delta_dtype) || !dtype_ok(merged_dtype)) return fail(RANDES_EINVAL, "unknown dtype");
     for (int64_t q = 0; q < (int64_t)n_tasks * n_layers; ++q)
-        if (!deltas[q]) return fail(RANDES_EINVAL, "NULL delta pointer");
+        if (!deltas[q] || !elem_aligned(deltas[q], delta_dtype)) return fail(RANDES_EINVAL, "NULL or misaligned input pointer");
     for (int32_t l = 0; l < n_layers; ++l)
-        if (!merged[l] || (base && !base[l])) return fail(RANDES_EINVAL, "NULL merged or base pointer");
+        if (!merged[l] || !elem_aligned(merged[l], merged_dtype) || (base && (!base[l] || !elem_aligned(base[l], delta_dtype))))
+            return fail(RANDES_EINVAL, "NULL or misaligned merged or base pointer");
 
     int dev;
     if ((rc = current_device(&dev))) return rc;
+    std::lock_guard<std::mutex> lock(g_mu);
     const int32_t tile_rows = g_merge_rows * 4 + g_max_wx_shift;   // both knobs, for the cache key
     std::string key;
     const int32_t head[6] = { base ? PLAN_MERGE_WEIGHTS : PLAN_MERGE, n_layers, n_tasks, (int32_t)delta_dtype, (int32_t)merged_dtype, tile_rows };
@@ -230,7 +233,6 @@ int merge_impl(const randes_layer *layers, int32_t n_layers,
     append(&key, merged, sizeof(void *) * (size_t)n_layers);
     if (base) append(&key, base, sizeof(void *) * (size_t)n_layers);
 
-    std::lock_guard<std::mutex> lock(g_mu);
     CachedPlan *cp = lookup(key, dev);
     if (!cp) {
         // the superposition must not overwrite its own inputs
@@ -326,10 +328,13 @@ int randes_retrieve(const randes_layer *layers, int32_t n_layers,
     if (!dtype_ok(merged_dtype) || !dtype_ok(base_dtype) || !dtype_ok(out_dtype)) return fail(RANDES_EINVAL, "unknown dtype");
     if (!std::isfinite(lambda)) return fail(RANDES_EINVAL, "lambda is not finite");
     for (int32_t l = 0; l < n_layers; ++l)
-        if (!merged[l] || !base[l] || !out[l]) return fail(RANDES_EINVAL, "NULL layer pointer");
+        if (!merged[l] || !base[l] || !out[l] || !elem_aligned(merged[l], merged_dtype) ||
+            !elem_aligned(base[l], base_dtype) || !elem_aligned(out[l], out_dtype))
+            return fail(RANDES_EINVAL, "NULL or misaligned layer pointer");
 
     int dev;
     if ((rc = current_device(&dev))) return rc;
+    std::lock_guard<std::mutex> lock(g_mu);
     const int32_t tile_rows = g_retrieve_rows * 4 + g_max_wx_shift;   // both knobs, for the cache key
     std::string key;
     const int32_t head[6] = { PLAN_RETRIEVE, n_layers, (int32_t)merged_dtype, (int32_t)base_dtype, (int32_t)out_dtype, tile_rows };
@@ -340,7 +345,6 @@ int randes_retrieve(const randes_layer *layers, int32_t n_layers,
     append(&key, out, sizeof(void *) * (size_t)n_layers);
     append(&key, &seed, sizeof(seed));
 
-    std::lock_guard<std::mutex> lock(g_mu);
     CachedPlan *cp = lookup(key, dev);
     if (!cp) {
         std::vector<Span> a, b;
@@ -404,10 +408,12 @@ int randes_update(const randes_layer *layers, int32_t n_layers,
     if (!merged || !delta) return fail(RANDES_EINVAL, "merged or delta is NULL");
     if (!dtype_ok(merged_dtype) || !dtype_ok(delta_dtype)) return fail(RANDES_EINVAL, "unknown dtype");
     for (int32_t l = 0; l < n_layers; ++l)
-        if (!merged[l] || !delta[l]) return fail(RANDES_EINVAL, "NULL layer pointer");
+        if (!merged[l] || !delta[l] || !elem_aligned(merged[l], merged_dtype) || !elem_aligned(delta[l], delta_dtype))
+            return fail(RANDES_EINVAL, "NULL or misaligned layer pointer");
 
     int dev;
     if ((rc = current_device(&dev))) return rc;
+    std::lock_guard<std::mutex> lock(g_mu);
     const int32_t tile_rows = g_retrieve_rows * 4 + g_max_wx_shift;   // both knobs, for the cache key
     std::string key;
     const int32_t head[5] = { PLAN_UPDATE, n_layers, (int32_t)merged_dtype, (int32_t)delta_dtype, tile_rows };
@@ -417,7 +423,6 @@ int randes_update(const randes_layer *layers, int32_t n_layers,
     append(&key, delta, sizeof(void *) * (size_t)n_layers);
     append(&key, &seed, sizeof(seed));
 
-    std::lock_guard<std::mutex> lock(g_mu);
     CachedPlan *cp = lookup(key, dev);
     if (!cp) {
         std::vector<Span> spans;
@@ -473,9 +478,12 @@ int randes_delta_stats(const randes_layer *layers, int32_t n_layers,
     if (!delta_a || !delta_b || !out3) return fail(RANDES_EINVAL, "delta_a, delta_b or out3 is NULL");
     if (!dtype_ok(dtype)) return fail(RANDES_EINVAL, "unknown dtype");
     for (int32_t l = 0; l < n_layers; ++l)
-        if (!delta_a[l] || !delta_b[l]) return fail(RANDES_EINVAL, "NULL layer pointer");
+        if (!delta_a[l] || !delta_b[l] || !elem_aligned(delta_a[l], dtype) || !elem_aligned(delta_b[l], dtype))
+            return fail(RANDES_EINVAL, "NULL or misaligned layer pointer");
+    if (((uintptr_t)out3 & 7u) != 0) return fail(RANDES_EINVAL, "out3 is not 8-byte aligned");
     int dev;
     if ((rc = current_device(&dev))) return rc;
+    std::lock_guard<std::mutex> lock(g_mu);
     std::string key;
     const int32_t head[4] = { PLAN_STATS, n_layers, (int32_t)dtype, g_retrieve_rows * 4 + g_max_wx_shift };
     append(&key, head, sizeof(head));
@@ -485,7 +493,6 @@ int randes_delta_stats(const randes_layer *layers, int32_t n_layers,
     append(&key, &seed_a, sizeof(seed_a));
     append(&key, &seed_b, sizeof(seed_b));
 
-    std::lock_guard<std::mutex> lock(g_mu);
     CachedPlan *cp = lookup(key, dev);
     if (!cp) {
         HostPlan hp;

@@ -81,6 +81,9 @@ def test_bad_arguments_are_error_codes_not_crashes(lib):
     assert lib.randes_merge(one, 1, ptr, 1, seeds, 7, ptr, 0, None) == EINVAL
     assert lib.randes_merge(one, 1, null, 1, seeds, 0, ptr, 0, None) == EINVAL
     assert lib.randes_merge(one, 1, ptr, 1, None, 0, ptr, 0, None) == EINVAL
+    odd = (ctypes.c_void_p * 1)(0x1002)   # not a multiple of the f32 element size
+    assert lib.randes_merge(one, 1, odd, 1, seeds, 0, ptr, 0, None) == EINVAL
+    assert lib.randes_retrieve(one, 1, ptr, 0, ptr, 0, 1, ctypes.c_float(1.0), odd, 0, None) == EINVAL
     bad_rows = (L * 1)(L(0, 4, 0, 3))
     assert lib.randes_merge(bad_rows, 1, ptr, 1, seeds, 0, ptr, 0, None) == EINVAL
     bad_flag = (L * 1)(L(4, 4, 0, 64))
