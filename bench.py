@@ -60,6 +60,7 @@ def parse():
     ap.add_argument("--cpu-sample-elems", type=int, default=1_600_000_000,
                     help="size of the oracle's sample (elements per model)")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the plain-streaming probe")
+    ap.add_argument("--no-extras", action="store_true", help="skip the LoRA front-end measurement")
     return ap.parse_args()
 
 
@@ -137,6 +138,44 @@ def ceilings(flats, merged_flat, out_flat):
         "add_%d_reads_1_write" % K: run(deltas[:K], m, True),
         "add_2_reads_1_write": run([m, base], o, True),
         "copy_1_read_1_write": run([base], o, True),
+    }
+
+
+def lora_extras():
+    """LoRA front-end on the T5-base LoRA shapes (72 adapter-carrying 768 x 768 matrices, rank 16, K = 8
+    models): batched materialisation of the 576 dense deltas, and the fused superposition that writes
+    the 72 merged matrices once.  Measured outside the timed region; write-bound, so GB/s of HBM."""
+    stack_full = wl.t5_base()
+    stack = [stack_full[t] for t in wl.t5_lora_targets(stack_full)]
+    layers = [(l.rows, l.cols, l.group, l.flags) for l in stack]
+    K, rank = 8, 16
+    factors = wl.make_lora_factors(stack, list(range(len(stack))), K, rank=rank, dtype="bf16", device="cuda")
+    Bs = [f[0] for per in factors for f in per]
+    As = [f[1] for per in factors for f in per]
+    batch = rb.LoraBatch(Bs, As)
+    seeds = [42 + i for i in range(K)]
+    fused = rb.LoraMerge(layers, factors, seeds, merged_dtype=torch.bfloat16)
+
+    def timed(fn, reps=10):
+        fn(); fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); fn(); b.record(); b.synchronize()
+            ts.append(a.elapsed_time(b))
+        return sorted(ts)[len(ts) // 2]
+    n_out = sum(l.rows * l.cols for l in stack)
+    in_bytes = K * sum((l.rows + l.cols) * rank * 2 for l in stack)
+    ms_mat = timed(lambda: batch.run(1.0))
+    ms_fused = timed(lambda: fused.run(1.0))
+    flop = 2.0 * K * n_out * rank
+    return {
+        "shapes": "72 x (768 x 768), rank 16, K = 8, bf16",
+        "materialize": {"ms": ms_mat, "GBs": (K * n_out * 2 + in_bytes) / (ms_mat * 1e-3) / 1e9,
+                        "TFLOPs": flop / (ms_mat * 1e-3) / 1e12},
+        "fused_merge": {"ms": ms_fused, "GBs": (n_out * 2 + in_bytes) / (ms_fused * 1e-3) / 1e9,
+                        "TFLOPs": flop / (ms_fused * 1e-3) / 1e12},
     }
 
 
@@ -258,6 +297,8 @@ def main():
     }
     if ceil is not None:
         result["config"]["plain_streaming_ceilings"] = ceil
+    if not args.no_extras:
+        result["config"]["lora_front_end"] = lora_extras()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(stack, deltas, base, seeds, dtype, n_req, args.cpu_sample_elems)
     print(json.dumps(result))

@@ -322,30 +322,40 @@ def lora_materialize_batched(Bs, As, scale=1.0, outs=None, out_dtype=None, strea
     return LoraBatch(Bs, As, outs, out_dtype).run(scale, stream)
 
 
+class LoraMerge:
+    """Marshalled arguments of a fused LoRA compress, built once and reused."""
+
+    def __init__(self, layers, factors, seeds, merged=None, merged_dtype=None):
+        lt = _layer_table(layers)
+        n_tasks = len(factors)
+        if n_tasks != len(seeds) or n_tasks < 1:
+            raise ValueError("%d seeds for %d models" % (len(seeds), n_tasks))
+        Bs = [f[0] for per in factors for f in per]
+        As = [f[1] for per in factors for f in per]
+        if len(Bs) != n_tasks * lt.n:
+            raise ValueError("need one (B, A) pair per model and layer")
+        rank = int(Bs[0].shape[1])
+        for q, (B, A) in enumerate(zip(Bs, As)):
+            rows, cols = lt.layers[q % lt.n][:2]
+            if tuple(B.shape) != (rows, rank) or tuple(A.shape) != (rank, cols) or A.dtype != Bs[0].dtype or B.dtype != Bs[0].dtype:
+                raise ValueError("factor pair %d does not fit layer %d x %d at rank %d" % (q, rows, cols, rank))
+        if merged is None:
+            merged = alloc_like_layers(lt, Bs[0].dtype if merged_dtype is None else merged_dtype, Bs[0].device)
+        self.lt, self.n_tasks, self.rank, self.merged = lt, n_tasks, rank, merged
+        self.bt, self.at, self.mt = PtrTable(Bs), PtrTable(As), _ptr_table(merged, lt)
+        self.sd = (ctypes.c_uint64 * n_tasks)(*[_u64(s) for s in seeds])
+
+    def run(self, scale=1.0, stream=None):
+        _check(lib().randes_lora_merge(self.lt.array, self.lt.n, self.bt.array, self.at.array, self.rank, self.n_tasks,
+                                       self.sd, ctypes.c_float(scale), self.bt.code, self.mt.array, self.mt.code,
+                                       _stream(stream)))
+        return self.merged
+
+
 def lora_merge(layers, factors, seeds, scale=1.0, merged=None, merged_dtype=None, stream=None):
     """Fused LoRA compress: ``factors[i][l] = (B, A)`` of model i, layer l (original
     position).  Returns the superposed dense layers, written once."""
-    lt = _layer_table(layers)
-    n_tasks = len(factors)
-    if n_tasks != len(seeds) or n_tasks < 1:
-        raise ValueError("%d seeds for %d models" % (len(seeds), n_tasks))
-    Bs = [f[0] for per in factors for f in per]
-    As = [f[1] for per in factors for f in per]
-    if len(Bs) != n_tasks * lt.n:
-        raise ValueError("need one (B, A) pair per model and layer")
-    rank = Bs[0].shape[1]
-    for q, (B, A) in enumerate(zip(Bs, As)):
-        rows, cols = lt.layers[q % lt.n][:2]
-        if tuple(B.shape) != (rows, rank) or tuple(A.shape) != (rank, cols) or A.dtype != Bs[0].dtype or B.dtype != Bs[0].dtype:
-            raise ValueError("factor pair %d does not fit layer %d x %d at rank %d" % (q, rows, cols, rank))
-    bt, at = PtrTable(Bs), PtrTable(As)
-    if merged is None:
-        merged = alloc_like_layers(lt, Bs[0].dtype if merged_dtype is None else merged_dtype, Bs[0].device)
-    mt = _ptr_table(merged, lt)
-    sd = (ctypes.c_uint64 * n_tasks)(*[_u64(s) for s in seeds])
-    _check(lib().randes_lora_merge(lt.array, lt.n, bt.array, at.array, rank, n_tasks, sd, ctypes.c_float(scale),
-                                   bt.code, mt.array, mt.code, _stream(stream)))
-    return merged
+    return LoraMerge(layers, factors, seeds, merged, merged_dtype).run(scale, stream)
 
 
 def set_tile_rows(merge_rows=0, retrieve_rows=0):
