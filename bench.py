@@ -32,7 +32,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # read for a plain copy of known size (FETCH_SIZE x 2.0000, WRITE_SIZE x 1.0000); see
 # profiles/llama_7b_bf16_k8_merge_retrieve.txt.  Valid for the kernels as committed with that profile;
 # set to None whenever a kernel changes until the counters are taken again.
-MEASURED_TRAFFIC_BYTES = {"llama_7b": {"retrieve": 40.429e9, "merge": 121.285e9}}
+MEASURED_TRAFFIC_BYTES = {"llama_7b": {"retrieve": 40.429e9, "merge": 121.286e9}}
 
 WORKLOADS = {
     # name: (stack fn, storage dtype, K, requests, delta std, per-task scales?)
