@@ -29,7 +29,7 @@ from paper_2505_11204_amd import workloads as wl        # noqa: E402
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same counters
-# read for a plain copy of known size (FETCH_SIZE x 2.0000, WRITE_SIZE x 1.0000); see
+# read for a plain copy of known size (FETCH_SIZE x 2.0000, WRITE_SIZE x 1.0000); the summary is
 # profiles/llama_7b_bf16_k8_merge_retrieve.txt.  Valid for the kernels as committed with that profile;
 # set to None whenever a kernel changes until the counters are taken again.
 MEASURED_TRAFFIC_BYTES = {"llama_7b": {"retrieve": 40.429e9, "merge": 121.286e9}}
@@ -182,8 +182,9 @@ def lora_extras():
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the path shards by rows with no communication; "
-              "see DESIGN.md); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        print("bench.py: this benchmark runs on one GPU only (the path would shard by rows with no "
+              "communication, so more GPUs add nothing to measure); --gpus %d is not supported" % args.gpus,
+              file=sys.stderr)
         sys.exit(2)
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
