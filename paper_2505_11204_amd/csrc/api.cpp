@@ -613,6 +613,8 @@ int randes_lora_materialize_batched(int32_t n, const void *const *Bs, const void
     std::vector<LoraSeg> segs((size_t)n);
     for (int32_t q = 0; q < n; ++q) {
         if (!Bs[q] || !As[q] || !outs[q]) return fail(RANDES_EINVAL, "NULL matrix pointer");
+        if (!elem_aligned(Bs[q], ab_dtype) || !elem_aligned(As[q], ab_dtype) || !elem_aligned(outs[q], out_dtype))
+            return fail(RANDES_EINVAL, "misaligned matrix pointer");
         if (rows[q] < 1 || cols[q] < 1) return fail(RANDES_EINVAL, "rows < 1 or cols < 1");
         if (rows[q] >= (int64_t)1 << 31 || cols[q] >= (int64_t)1 << 31) return fail(RANDES_ENOTSUP, "rows or cols >= 2^31");
         LoraItem &it = items[(size_t)q];
@@ -641,9 +643,10 @@ int randes_lora_merge(const randes_layer *layers, int32_t n_layers,
     if (!dtype_ok(ab_dtype) || !dtype_ok(merged_dtype)) return fail(RANDES_EINVAL, "unknown dtype");
     if (!std::isfinite(scale)) return fail(RANDES_EINVAL, "scale is not finite");
     for (int64_t q = 0; q < (int64_t)n_tasks * n_layers; ++q)
-        if (!Bs[q] || !As[q]) return fail(RANDES_EINVAL, "NULL factor pointer");
+        if (!Bs[q] || !As[q] || !elem_aligned(Bs[q], ab_dtype) || !elem_aligned(As[q], ab_dtype))
+            return fail(RANDES_EINVAL, "NULL or misaligned factor pointer");
     for (int32_t l = 0; l < n_layers; ++l)
-        if (!merged[l]) return fail(RANDES_EINVAL, "NULL merged pointer");
+        if (!merged[l] || !elem_aligned(merged[l], merged_dtype)) return fail(RANDES_EINVAL, "NULL or misaligned merged pointer");
     std::vector<std::vector<int32_t>> src((size_t)n_tasks);
     for (int32_t i = 0; i < n_tasks; ++i) {
         rc = build_source_table(layers, n_layers, seeds[i], &src[(size_t)i], &why);

@@ -117,6 +117,10 @@ def test_bad_arguments_are_error_codes_not_crashes(lib):
     assert lib.randes_lora_merge(one, 1, ptr, null, 4, 1, seeds, ctypes.c_float(1.0), 0, ptr, 0, None) == EINVAL
     assert lib.randes_lora_merge(one, 1, ptr, ptr, 4, rb.MAX_TASKS + 1, seeds, ctypes.c_float(1.0), 0, ptr, 0, None) == ENOTSUP
     assert lib.randes_lora_merge(one, 1, ptr, ptr, 4, 1, seeds, ctypes.c_float(float("nan")), 0, ptr, 0, None) == EINVAL
+    assert lib.randes_lora_merge(one, 1, odd, ptr, 4, 1, seeds, ctypes.c_float(1.0), 0, ptr, 0, None) == EINVAL
+    assert lib.randes_lora_merge(one, 1, ptr, ptr, 4, 1, seeds, ctypes.c_float(1.0), 0, odd, 0, None) == EINVAL
+    assert lib.randes_lora_materialize(ctypes.c_void_p(0x1001), ptr, 4, 4, 2, ctypes.c_float(1.0), 1, ptr, 1, None) == EINVAL
+    assert b"misaligned" in lib.randes_strerror(EINVAL)
     assert lib.randes_probe_stream(ptr, 0, ptr, 16384, 1, None) == EINVAL
     assert lib.randes_probe_stream(ptr, 9, ptr, 16384, 1, None) == EINVAL
     assert lib.randes_probe_stream(ptr, 1, ptr, 1000, 1, None) == EINVAL
