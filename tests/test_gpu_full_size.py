@@ -3,6 +3,8 @@ configuration the benchmark times.  ViT-B/32-shaped: every element against the
 oracle.  The larger stacks are generated on the device; the oracle recomputes
 sampled rows of every layer (first/last rows, tile edges, random rows), which
 is exact because neither the sign masks nor the permutations depend on the row."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -136,3 +138,51 @@ def test_t5_base_lora_variant_sampled_rows():
 def test_llama_7b_bf16_sampled_rows():
     K = 8
     _sampled_stack_parity(wl.llama_7b(), K, "bf16", [42 + i for i in range(K)], 1.0, [0, 3, 7], 5e-4)
+
+
+def _every_element_parity(stack, K, dtype, seeds, lam, retrieve_tasks, delta_std, scales=None):
+    """Whole-stack comparison: inputs generated on the device, copied to the host, and every
+    element of the merged stack and of the retrieved stacks compared bit for bit."""
+    layers = layers_of(stack)
+    base, deltas = wl.make_inputs(stack, K, dtype=dtype, device="cuda", data_seed=1234,
+                                  delta_std=delta_std, scales=scales)
+    gm = rb.merge(layers, deltas, seeds)
+    torch.cuda.synchronize()
+    host_d = []
+    for i, per in enumerate(deltas):
+        host_d.append([wl.to_numpy(t) for t in per])
+        print("model %d of %d on the host" % (i + 1, K), flush=True)
+    want_m = oracle.merge(layers, host_d, seeds, CODE[dtype], CODE[dtype], n_threads=16)
+    print("oracle merge done", flush=True)
+    del host_d
+    for l in range(len(stack)):
+        _same_bits(wl.to_numpy(gm[l]), want_m[l], "merged layer %d" % l)
+    host_b = [wl.to_numpy(t) for t in base]
+    out = rb.alloc_like_layers(layers, TD[dtype])
+    for i in retrieve_tasks:
+        rb.retrieve(layers, gm, base, seeds[i], lam, out=out)
+        torch.cuda.synchronize()
+        want_o = oracle.retrieve(layers, want_m, host_b, seeds[i], lam, CODE[dtype], CODE[dtype], CODE[dtype],
+                                 n_threads=16)
+        for l in range(len(stack)):
+            _same_bits(wl.to_numpy(out[l]), want_o[l], "task %d layer %d" % (i, l))
+        print("task %d compared" % i, flush=True)
+        del want_o
+
+
+def test_t5_base_bf16_every_element():
+    _every_element_parity(wl.t5_base(), 8, "bf16", [42 + i for i in range(8)], 1.0, [0, 5], 1e-3)
+
+
+def test_vit_l14_twenty_tasks_every_element():
+    K = 20
+    _every_element_parity(wl.vit_l14(), K, "f32", [42 + i for i in range(K)], 1.0, [0, 19], 1e-3,
+                          wl.task_scales(K, 1234))
+
+
+@pytest.mark.skipif(os.environ.get("RANDES_TEST_WHOLE_7B") != "1",
+                    reason="opt-in (RANDES_TEST_WHOLE_7B=1): copies 135 GB to the host and runs the oracle over "
+                           "all 6.7e9 elements, a few minutes; the sampled-row test covers every layer routinely")
+def test_llama_7b_bf16_every_element():
+    K = 8
+    _every_element_parity(wl.llama_7b(), K, "bf16", [42 + i for i in range(K)], 1.0, [3], 5e-4)
