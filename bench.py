@@ -24,6 +24,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 from paper_2505_11204_amd import binding as rb          # noqa: E402
+from paper_2505_11204_amd import placement              # noqa: E402
 from paper_2505_11204_amd import workloads as wl        # noqa: E402
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
@@ -59,6 +60,10 @@ def parse():
                          "counters collected over this command can be scaled by a kernel of known traffic")
     ap.add_argument("--cpu-sample-elems", type=int, default=1_600_000_000,
                     help="size of the oracle's sample (elements per model)")
+    ap.add_argument("--placement", choices=("groups", "plain"), default="groups",
+                    help="groups: find the memory's address groups by timing copies and place read and "
+                         "write streams in different ones (stacks of 8 GiB and more); plain: one "
+                         "allocation per stack, wherever the allocator puts it")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the plain-streaming probe")
     ap.add_argument("--no-extras", action="store_true", help="skip the LoRA front-end measurement")
     return ap.parse_args()
@@ -213,12 +218,40 @@ def main():
     scales = wl.task_scales(K, 1234) if scaled else None
     rb.set_tile_rows(args.merge_rows, args.retrieve_rows)
 
+    td = wl.torch_dtype(dtype)
+    stack_elems = wl.stack_elements(stack, td)
+    placed = {"policy": "plain"}
+    place = merged_into = out_into = None
+    if args.placement == "groups" and stack_elems * eb >= (8 << 30):
+        # everything but a reserve for temporaries goes into one allocation, cut by measurement
+        free_bytes, _ = torch.cuda.mem_get_info()
+        arena = placement.Arena(free_bytes - (12 << 30))
+        t_cls = time.perf_counter()
+        labels = arena.classify()
+        t_cls = time.perf_counter() - t_cls
+        layout = placement.plan_serving_layout(labels, arena.chunk_bytes, stack_elems * eb, K)
+        placed = {"policy": "plain (no usable address groups found)", "classify_s": t_cls,
+                  "runs_gib": [(g, a, b) for g, a, b in placement.runs_of(labels)]}
+        if layout is not None:
+            gib = lambda off: round(off / (1 << 30), 2)      # noqa: E731
+            placed.update({
+                "policy": "merged and base in one address group, out across the boundary of two others, "
+                          "deltas in what is left of every group but the first",
+                "read_group": layout["read_group"], "write_groups": layout["write_groups"],
+                "offsets_gib": {"merged": gib(layout["merged"]), "base": gib(layout["base"]),
+                                "out": gib(layout["out"]), "deltas": [gib(d) for d in layout["deltas"]]}})
+            place = lambda who: arena.flat(layout["base"] if who == "base" else layout["deltas"][who],   # noqa: E731
+                                           stack_elems, td)
+            merged_into = arena.flat(layout["merged"], stack_elems, td)
+            out_into = arena.flat(layout["out"], stack_elems, td)
+        else:
+            del arena
+            torch.cuda.empty_cache()
     flats = []
     base, deltas = wl.make_inputs(stack, K, dtype=dtype, device="cuda", data_seed=1234,
-                                  delta_std=delta_std, scales=scales, flats=flats)
-    td = wl.torch_dtype(dtype)
-    merged_flat, merged = wl.alloc_stack(stack, td, "cuda")
-    out_flat, out = wl.alloc_stack(stack, td, "cuda")
+                                  delta_std=delta_std, scales=scales, flats=flats, place=place)
+    merged_flat, merged = wl.alloc_stack(stack, td, "cuda", into=merged_into)
+    out_flat, out = wl.alloc_stack(stack, td, "cuda", into=out_into)
     lt = rb.LayerTable(layers)
     t_deltas = rb.PtrTable([t for per in deltas for t in per], lt)
     t_merged, t_base, t_out = rb.PtrTable(merged, lt), rb.PtrTable(base, lt), rb.PtrTable(out, lt)
@@ -320,6 +353,7 @@ def main():
                            "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload, {}).get("merge")},
     }
     result["config"]["first_call_with_table_build_and_upload"] = first
+    result["config"]["hbm_placement"] = placed
     if ceil is not None:
         result["config"]["plain_streaming_ceilings"] = ceil
     if not args.no_extras:

@@ -91,15 +91,27 @@ def _aligned(count, elem_bytes, align=256):
     return (count + per - 1) // per * per
 
 
-def alloc_stack(stack, dtype, device):
+def stack_elements(stack, dtype):
+    """Elements of the flat buffer of :func:`alloc_stack` (layers padded to 256 bytes)."""
+    eb = torch.empty((), dtype=dtype).element_size()
+    return sum(_aligned(l.rows * l.cols, eb) for l in stack)
+
+
+def alloc_stack(stack, dtype, device, into=None):
     """One flat buffer holding every layer (each 256-byte aligned), plus the
-    list of per-layer 2-D views into it."""
+    list of per-layer 2-D views into it.  ``into`` is a flat tensor of
+    :func:`stack_elements` elements to use instead of a new allocation."""
     eb = torch.empty((), dtype=dtype).element_size()
     offs, total = [], 0
     for l in stack:
         offs.append(total)
         total += _aligned(l.rows * l.cols, eb)
-    flat = torch.empty(total, dtype=dtype, device=device)
+    if into is not None:
+        if into.dtype != dtype or into.dim() != 1 or into.numel() != total:
+            raise ValueError("`into` must be a flat %s tensor of %d elements" % (dtype, total))
+        flat = into
+    else:
+        flat = torch.empty(total, dtype=dtype, device=device)
     views = [flat[o:o + l.rows * l.cols].view(l.rows, l.cols) for o, l in zip(offs, stack)]
     return flat, views
 
@@ -124,7 +136,8 @@ def task_scales(n_tasks, data_seed, low=0.5, high=2.0):
 
 
 def make_inputs(stack, n_tasks, dtype="f32", device="cpu", data_seed=1234,
-                base_std=0.02, delta_std=1e-3, scales=None, with_base=True, flats=None):
+                base_std=0.02, delta_std=1e-3, scales=None, with_base=True, flats=None,
+                place=None):
     """Seeded synthetic base weights and deltas.
 
     Returns ``(base_views, delta_views)`` where ``delta_views[i][l]`` is model
@@ -132,20 +145,22 @@ def make_inputs(stack, n_tasks, dtype="f32", device="cpu", data_seed=1234,
     delta_i ~ N(0, (delta_std * scales[i])^2), i.i.d.; values are rounded to
     ``dtype`` by torch.  The same (device, seed) always gives the same bits.
     If ``flats`` is a list, the flat backing buffers (base first, then one per
-    model) are appended to it.
+    model) are appended to it.  ``place("base")`` / ``place(i)``, if given,
+    returns the flat tensor a stack is to live in (see :func:`alloc_stack`);
+    the values drawn do not depend on it.
     """
     td = torch_dtype(dtype)
     g = torch.Generator(device=device)
     g.manual_seed(data_seed)
     base = None
     if with_base:
-        bflat, base = alloc_stack(stack, td, device)
+        bflat, base = alloc_stack(stack, td, device, into=place("base") if place else None)
         fill_normal(bflat, base_std, g)
         if flats is not None:
             flats.append(bflat)
     deltas = []
     for i in range(n_tasks):
-        dflat, dviews = alloc_stack(stack, td, device)
+        dflat, dviews = alloc_stack(stack, td, device, into=place(i) if place else None)
         fill_normal(dflat, delta_std * (scales[i] if scales else 1.0), g)
         deltas.append(dviews)
         if flats is not None:

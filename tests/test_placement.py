@@ -1,0 +1,101 @@
+"""Host logic of the HBM placement: finding address groups from copy rates and packing
+the stacks of a serving set-up into them.  The rates here come from a model of the
+behaviour measured on the device (same group slow, different groups fast, a little
+noise, a rare slow misread); no GPU is involved."""
+import random
+
+import pytest
+
+from paper_2505_11204_amd import placement as pl
+
+GIB = 1 << 30
+STACK = 13476298752          # bytes of one Llama-7B-shaped bf16 stack
+
+
+def rates_of(groups, noise=20.0, seed=0, outliers=0.02):
+    rnd = random.Random(seed)
+
+    def rate(r, w):
+        v = (5780.0 if groups[r] == groups[w] else 6010.0) + rnd.uniform(-noise, noise)
+        if rnd.random() < outliers:
+            v -= 200.0
+        return v
+    return rate
+
+
+def same_partition(truth, labels, slack=1):
+    """Equal up to renaming, ignoring chunks within `slack` of a true boundary."""
+    edges = [c for c in range(1, len(truth)) if truth[c] != truth[c - 1]]
+    m = {}
+    for c, (a, b) in enumerate(zip(truth, labels)):
+        if any(abs(c - e) <= slack and c >= e - slack for e in edges):
+            continue
+        if m.setdefault(a, b) != b:
+            return False
+    return len(set(m.values())) == len(m)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_three_contiguous_groups_are_found(seed):
+    truth = [0] * 96 + [1] * 96 + [2] * 82
+    labels = pl.classify_chunks(len(truth), rates_of(truth, seed=seed))
+    assert same_partition(truth, labels)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_groups_in_several_runs_are_found(seed):
+    truth = list("X" * 64 + "Y" * 64 + "X" * 32 + "Z" * 32 + "Y" * 24 + "Z" * 32 + "Y" * 8 + "Z" * 22)
+    labels = pl.classify_chunks(len(truth), rates_of(truth, seed=seed))
+    assert same_partition(truth, labels)
+
+
+def test_uniform_memory_is_one_group_and_gets_no_layout():
+    rnd = random.Random(5)
+    labels = pl.classify_chunks(64, lambda r, w: 6000.0 + rnd.uniform(-40, 40) - (200 if rnd.random() < 0.03 else 0))
+    assert labels == [0] * 64
+    assert pl.plan_serving_layout(labels, GIB, STACK, 8) is None
+
+
+def test_runs_of():
+    assert pl.runs_of([0, 0, 1, 1, 1, 0]) == [(0, 0, 2), (1, 2, 5), (0, 5, 6)]
+    assert pl.runs_of([3]) == [(3, 0, 1)]
+
+
+def check_layout(labels, lay, n_models):
+    spans = [(lay["merged"], "merged"), (lay["base"], "base"), (lay["out"], "out")]
+    spans += [(d, "delta") for d in lay["deltas"]]
+    assert len(lay["deltas"]) == n_models
+    # inside the allocation, 256-byte aligned, pairwise disjoint
+    for off, _ in spans:
+        assert off % 256 == 0 and 0 <= off and off + STACK <= len(labels) * GIB
+    order = sorted(off for off, _ in spans)
+    assert all(b - a >= STACK for a, b in zip(order, order[1:]))
+
+    def groups_touched(off):
+        return {labels[c] for c in range(off // GIB, (off + STACK - 1) // GIB + 1)}
+    R = lay["read_group"]
+    assert groups_touched(lay["merged"]) == {R} and groups_touched(lay["base"]) == {R}
+    assert groups_touched(lay["out"]) == set(lay["write_groups"]) and R not in lay["write_groups"]
+    # the output stack lies half and half across the boundary
+    edge = next(c for c in range(lay["out"] // GIB, len(labels)) if labels[c] != labels[lay["out"] // GIB]) * GIB
+    assert abs((edge - lay["out"]) - STACK / 2) <= 256
+    for d in lay["deltas"]:
+        assert R not in groups_touched(d)
+
+
+def test_layout_on_contiguous_groups():
+    labels = [1] * 96 + [0] * 96 + [2] * 82
+    lay = pl.plan_serving_layout(labels, GIB, STACK, 8)
+    check_layout(labels, lay, 8)
+
+
+def test_layout_on_groups_in_several_runs():
+    labels = [0] * 64 + [1] * 64 + [0] * 32 + [2] * 32 + [1] * 24 + [2] * 32 + [1] * 8 + [2] * 22
+    lay = pl.plan_serving_layout(labels, GIB, STACK, 8)
+    check_layout(labels, lay, 8)
+
+
+def test_layout_needs_room():
+    labels = [0] * 20 + [1] * 20 + [2] * 20          # 60 GiB cannot hold eleven 12.55 GiB stacks
+    assert pl.plan_serving_layout(labels, GIB, STACK, 8) is None
+    assert pl.plan_serving_layout([0] * 96 + [1] * 96, GIB, STACK, 8) is None     # two groups only
