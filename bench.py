@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # read for a plain copy of known size (FETCH_SIZE x 2.0000, WRITE_SIZE x 1.0000); the summary is
 # profiles/llama_7b_bf16_k8_merge_retrieve.txt.  Valid for the kernels as committed with that profile;
 # set to None whenever a kernel changes until the counters are taken again.
-MEASURED_TRAFFIC_BYTES = {"llama_7b": {"retrieve": 40.429e9, "merge": 121.286e9}}
+MEASURED_TRAFFIC_BYTES = {"llama_7b": {"retrieve": 40.429e9, "merge": 121.285e9}}
 
 WORKLOADS = {
     # name: (stack fn, storage dtype, K, requests, delta std, per-task scales?)
@@ -225,13 +225,17 @@ def main():
     if args.placement == "groups" and stack_elems * eb >= (8 << 30):
         # everything but a reserve for temporaries goes into one allocation, cut by measurement
         free_bytes, _ = torch.cuda.mem_get_info()
-        arena = placement.Arena(free_bytes - (12 << 30))
-        t_cls = time.perf_counter()
-        labels = arena.classify()
-        t_cls = time.perf_counter() - t_cls
-        layout = placement.plan_serving_layout(labels, arena.chunk_bytes, stack_elems * eb, K)
-        placed = {"policy": "plain (no usable address groups found)", "classify_s": t_cls,
-                  "runs_gib": [(g, a, b) for g, a, b in placement.runs_of(labels)]}
+        arena = layout = None
+        try:
+            arena = placement.Arena(free_bytes - (12 << 30))
+            t_cls = time.perf_counter()
+            labels = arena.classify()
+            t_cls = time.perf_counter() - t_cls
+            layout = placement.plan_serving_layout(labels, arena.chunk_bytes, stack_elems * eb, K)
+            placed = {"policy": "plain (no usable address groups found)", "classify_s": t_cls,
+                      "runs_gib": [(g, a, b) for g, a, b in placement.runs_of(labels)]}
+        except (RuntimeError, ValueError) as e:      # the large allocation itself failed
+            placed = {"policy": "plain (arena not available: %s)" % str(e).splitlines()[0][:120]}
         if layout is not None:
             gib = lambda off: round(off / (1 << 30), 2)      # noqa: E731
             placed.update({
