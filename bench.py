@@ -195,6 +195,32 @@ def lora_extras():
     }
 
 
+def widened_rows(lt, per_model_tables, t_deltas, t_merged, t_base, seeds, n_elem, eb, K):
+    """The other streaming entry points on the same stacks, after the timed region (they overwrite
+    the merged stack): hot add of one model, the diagnostics reduction, merge from weights."""
+    def timed(fn, reps=4):
+        fn()
+        ts = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); fn(); b.record(); b.synchronize()
+            ts.append(a.elapsed_time(b))
+        return sorted(ts)[len(ts) // 2]
+    stats_out = torch.empty(3, dtype=torch.float64, device="cuda")
+    rows = {
+        "hot_add (reads delta + merged, writes merged)":
+            (3 * eb, timed(lambda: rb.update(lt, t_merged, per_model_tables[0], seeds[0]))),
+        "delta_stats (reads two deltas)":
+            (2 * eb, timed(lambda: rb.delta_stats(lt, per_model_tables[0], seeds[0], per_model_tables[1 % K],
+                                                  seeds[1 % K], out=stats_out))),
+        # timing only: the delta stacks stand in for fine-tuned weights.  Task i's term of slot l is
+        # weights_i[src_i(l)] - base[src_i(l)]: the base layer differs per task, so 2K read streams.
+        "merge_from_weights (reads K weights + K base layers, writes merged)":
+            ((2 * K + 1) * eb, timed(lambda: rb.merge_weights(lt, t_deltas, t_base, seeds, merged=t_merged))),
+    }
+    return {name: {"ms": ms, "GBs": n_elem * bpe / (ms * 1e-3) / 1e9} for name, (bpe, ms) in rows.items()}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -361,6 +387,9 @@ def main():
     if ceil is not None:
         result["config"]["plain_streaming_ceilings"] = ceil
     if not args.no_extras:
+        per_model = [rb.PtrTable(deltas[i], lt) for i in range(min(K, 2))]
+        result["config"]["other_entry_points"] = widened_rows(lt, per_model, t_deltas, t_merged, t_base, seeds,
+                                                              n_elem, eb, K)
         result["config"]["lora_front_end"] = lora_extras()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(stack, deltas, base, seeds, dtype, n_req, args.cpu_sample_elems)
