@@ -248,7 +248,7 @@ def main():
     stack_elems = wl.stack_elements(stack, td)
     placed = {"policy": "plain"}
     place = merged_into = out_into = None
-    if args.placement == "groups" and stack_elems * eb >= (8 << 30):
+    if args.placement == "groups" and stack_elems * eb >= (256 << 20):
         # everything but a reserve for temporaries goes into one allocation, cut by measurement
         free_bytes, _ = torch.cuda.mem_get_info()
         arena = layout = None
