@@ -18,10 +18,10 @@
 //
 // Operand layout of the 32x32 MFMAs: lane L supplies row (L % 32) of the left operand and column
 // (L % 32) of the right operand for the depth slice owned by lane half (L / 32); accumulator
-// register v of lane L is row 8*(v/4) + 4*(L/32) + (v%4), column L % 32 of the product.  For bf16
-// output the product is formed transposed (A^T-slice as left operand, B^T as right), so that a lane
-// ends up with four adjacent output columns per accumulator quad and can hand them to LDS 8 bytes
-// at a time.
+// register v of lane L is row 8*(v/4) + 4*(L/32) + (v%4), column L % 32 of the product.  The
+// product is formed transposed (A^T-slice as left operand, B^T as right), so that a lane ends up
+// with four adjacent output columns per accumulator quad and can hand them to LDS 8 (bf16) or 16
+// (binary32) bytes at a time; rows then leave LDS as 16-byte pieces of contiguous row segments.
 #include <hip/hip_runtime.h>
 
 #include "device_util.hpp"
@@ -47,16 +47,18 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 
 constexpr int KCH = 16;                 // rank slice per staging step
 constexpr int AS_STRIDE = LORA_TILE_N + 8;   // elements per staged depth row (keeps rows 16-byte aligned)
-constexpr int ST_STRIDE = 136;          // bf16 elements per staged output row (272 B)
+constexpr int ST_ROW_BYTES = 272;       // staged output row: 128 bf16 or 64 binary32 columns, plus 16 bytes
+constexpr int ST_STRIDE = ST_ROW_BYTES / 2;     // in bf16 elements
+constexpr int ST_STRIDE_F = ST_ROW_BYTES / 4;   // in binary32 elements
 
 template <int DTAB, int DTO>
 __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t n_items, const LoraSeg *segs,
                                                   const uint32_t *coarse, int32_t rank, float scale)
 {
     constexpr int AT_BYTES = KCH * AS_STRIDE * (DTAB == DT_BF16 ? 2 : 4);
-    constexpr int ST_BYTES = (DTO == DT_BF16) ? WAVES * LORA_TILE_M * ST_STRIDE * 2 : 16;
+    constexpr int ST_BYTES = WAVES * LORA_TILE_M * ST_ROW_BYTES;
     __shared__ __attribute__((aligned(16))) char smem[AT_BYTES];       // the staged slab of A
-    __shared__ __attribute__((aligned(16))) char sstage[ST_BYTES];     // bf16 output staging, one region per wave
+    __shared__ __attribute__((aligned(16))) char sstage[ST_BYTES];     // output staging, one region per wave
     __shared__ uint32_t sbits[LORA_TILE_N / 32];
 
     const uint32_t bid = blockIdx.x;
@@ -194,10 +196,7 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
                         frag[b].w = (uint32_t)col[6 * AS_STRIDE] | ((uint32_t)col[7 * AS_STRIDE] << 16);
                     }
                     const u32x4 bq = frag[b];
-                    if constexpr (DTO == DT_BF16)
-                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bq), av, acc[b], 0, 0, 0);
-                    else
-                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8, bq), acc[b], 0, 0, 0);
+                    acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bq), av, acc[b], 0, 0, 0);
                 }
             } else {
                 const float *As = (const float *)smem;
@@ -210,10 +209,7 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
                         const uint32_t c = wave * 128u + (uint32_t)b * 32u + l32;
-                        if constexpr (DTO == DT_BF16)
-                            acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(As[kk * AS_STRIDE + c], a, acc[b], 0, 0, 0);
-                        else
-                            acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, As[kk * AS_STRIDE + c], acc[b], 0, 0, 0);
+                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(As[kk * AS_STRIDE + c], a, acc[b], 0, 0, 0);
                     }
                 }
             }
@@ -221,23 +217,49 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
     }
 
     // ---- epilogue ----
-    const int32_t wcol0 = col0 + (int32_t)wave * 128;    // first column of this wave's 32 x 128 block
+    // transposed product: this lane holds output row l32, columns b*32 + 8*g + 4*half + (0..3) of
+    // its wave's 32 x 128 block in acc[b][4*g .. 4*g+3]
+    const int32_t wcol0 = col0 + (int32_t)wave * 128;    // first column of this wave's block
     if constexpr (DTO == DT_F32) {
+        // two passes of 64 columns through the wave's staging region
+        float *stg = (float *)sstage + wave * (LORA_TILE_M * ST_STRIDE_F);
         RANDES_GLOBAL float *out = (RANDES_GLOBAL float *)it.out;
+        const bool o_vec_ok = (cols % 4 == 0) && (((uintptr_t)it.out & 15u) == 0);
+        const int c4 = (int)(lane & 15u) * 4;
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int32_t c = wcol0 + b * 32 + (int32_t)l32;
+        for (int h = 0; h < 2; ++h) {
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave's reads of the previous pass are done
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int32_t r = row0 + 8 * (v / 4) + 4 * (int32_t)half + (v % 4);
-                if (r < rows && c < cols) out[(int64_t)r * cols + c] = scale * acc[b][v];
+            for (int bb = 0; bb < 2; ++bb)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    u32x4 q;
+                    q.x = f2u(scale * acc[2 * h + bb][4 * g + 0]); q.y = f2u(scale * acc[2 * h + bb][4 * g + 1]);
+                    q.z = f2u(scale * acc[2 * h + bb][4 * g + 2]); q.w = f2u(scale * acc[2 * h + bb][4 * g + 3]);
+                    *(u32x4 *)(stg + (int)l32 * ST_STRIDE_F + bb * 32 + 8 * g + 4 * (int)half) = q;
+                }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the wave's writes have landed before any lane reads
+#pragma unroll
+            for (int p = 0; p < 8; ++p) {
+                const int r = p * 4 + (int)(lane >> 4);
+                const int32_t gr = row0 + r, gc = wcol0 + h * 64 + c4;
+                if (gr < rows && gc < cols) {
+                    const u32x4 q = *(const u32x4 *)(stg + r * ST_STRIDE_F + c4);
+                    if (o_vec_ok) {
+                        __builtin_nontemporal_store(q, (RANDES_GLOBAL u32x4 *)(out + (int64_t)gr * cols + gc));
+                    } else {
+                        const uint32_t w[4] = { q.x, q.y, q.z, q.w };
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if (gc + j < cols) out[(int64_t)gr * cols + gc + j] = u2f(w[j]);
+                    }
+                }
             }
         }
     } else {
         // each wave stages and drains its own region: ordering inside one wave is all that is needed
         uint16_t *stg = (uint16_t *)sstage + wave * (LORA_TILE_M * ST_STRIDE);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave's reads of the previous block are done
-        // transposed product: this lane holds output row l32, columns b*32 + 8*g + 4*half + (0..3)
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
