@@ -546,7 +546,9 @@ int run_lora(std::vector<LoraItem> &items, const std::vector<LoraSeg> &segs, int
              int ab_dtype, int out_dtype, void *hip_stream)
 {
     uint64_t tiles = 0;
+    uint32_t max_seg = 1;
     for (LoraItem &it : items) {
+        max_seg = std::max(max_seg, it.n_seg);
         it.tiles_x = (uint32_t)(((int64_t)it.cols + LORA_TILE_N - 1) / LORA_TILE_N);
         it.tile_begin = (uint32_t)tiles;
         tiles += (uint64_t)it.tiles_x * (uint64_t)(((int64_t)it.rows + LORA_TILE_M * LORA_ROW_TILES - 1) / (LORA_TILE_M * LORA_ROW_TILES));
@@ -590,7 +592,8 @@ int run_lora(std::vector<LoraItem> &items, const std::vector<LoraSeg> &segs, int
     }
     hipError_t e = launch_lora((const LoraItem *)cp->blob, (int32_t)items.size(),
                                (const LoraSeg *)((const char *)cp->blob + items_bytes),
-                               (const uint32_t *)((const char *)cp->blob + items_bytes + segs_bytes), (uint32_t)tiles, rank, scale,
+                               (const uint32_t *)((const char *)cp->blob + items_bytes + segs_bytes), (uint32_t)tiles,
+                               (int32_t)max_seg, rank, scale,
                                ab_dtype, out_dtype, (hipStream_t)hip_stream);
     if (e != hipSuccess) return hip_fail(e, "lora launch");
     return RANDES_OK;

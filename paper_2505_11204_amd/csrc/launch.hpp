@@ -36,9 +36,10 @@ struct LoraSeg {
     const void *A;        // rank x cols
     uint32_t key_lo, key_hi, layer_id, flip;   // the sign diagonal D (flip = 0: identity)
 };
-// coarse_dev[i] = matrix holding workgroup 64 * i, for i = 0 .. ceil(n_tiles / 64).
+// coarse_dev[i] = matrix holding workgroup 64 * i, for i = 0 .. ceil(n_tiles / 64); max_seg = most
+// segments of any matrix (chooses the kernel variant).
 hipError_t launch_lora(const LoraItem *items_dev, int32_t n_items, const LoraSeg *segs_dev, const uint32_t *coarse_dev,
-                       uint32_t n_tiles, int32_t rank, float scale, int dt_ab, int dt_out, hipStream_t s);
+                       uint32_t n_tiles, int32_t max_seg, int32_t rank, float scale, int dt_ab, int dt_out, hipStream_t s);
 
 // Columns per lane of the vector kernels for a call whose widest-count stream
 // holds bf16 (8) or only f32 (4).

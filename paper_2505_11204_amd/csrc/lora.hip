@@ -8,11 +8,12 @@
 // sum_i (B_i A_i) D_i = [B_1 .. B_K] [A_1 D_1; ..; A_K D_K], a rank K*r contraction.
 //
 // A workgroup (4 waves) owns 512 columns and LORA_ROW_TILES consecutive blocks of 32 rows; per block
-// each wave owns 32 x 128 = four 32x32 MFMA accumulators.  With a single segment of rank <= 16 the
-// staged slab of A serves all row blocks of the workgroup.  Per 16-deep slice of the rank the workgroup stages A's 16 x 512 slab, sign-flipped,
-// into LDS with 16-byte accesses (row-major, as in memory); a lane then gathers the 8 depth values
-// of its column with 2-byte LDS reads, which are conflict-free because neighbouring lanes read
-// neighbouring columns.  B's rows come straight from global memory (16 bytes per lane).  bf16
+// each wave owns 32 x 128 = four 32x32 MFMA accumulators.  Per 16-deep slice of the depth (segments
+// x rank) the workgroup stages A's 16 x 512 slab, sign-flipped, into LDS with 16-byte accesses
+// (row-major, as in memory); a lane then gathers the 8 depth values of its column with 2-byte LDS
+// reads, which are conflict-free because neighbouring lanes read neighbouring columns.  Up to 8
+// slices (one rank-16 adapter, or 8 of them superposed) are staged and gathered once per workgroup
+// and kept in registers for all its row blocks; deeper products stage per row block.  B's rows come straight from global memory (16 bytes per lane).  bf16
 // results go back through LDS so that every lane stores 16 contiguous bytes.  The kernel is bound
 // by the output write.
 //
@@ -50,11 +51,147 @@ constexpr int AS_STRIDE = LORA_TILE_N + 8;   // elements per staged depth row (k
 constexpr int ST_ROW_BYTES = 272;       // staged output row: 128 bf16 or 64 binary32 columns, plus 16 bytes
 constexpr int ST_STRIDE = ST_ROW_BYTES / 2;     // in bf16 elements
 constexpr int ST_STRIDE_F = ST_ROW_BYTES / 4;   // in binary32 elements
+constexpr int LORA_RESIDENT_MAX = 8;    // depth slices whose operand fragments a wave can keep in registers
 
-template <int DTAB, int DTO>
+// Sign bits of the tile's 512 columns for one segment: four generator blocks (tiles start on
+// multiples of 512).  Threads 0..3; made visible by the barrier that precedes the staging.
+__device__ __forceinline__ void lora_sign_bits(uint32_t *sbits, const LoraSeg &S, int32_t col0, uint32_t tid)
+{
+    if (tid < LORA_TILE_N / 128) {
+        u32x4_t o;
+        if (S.flip) o = sign_block(S.key_lo, S.key_hi, S.layer_id, ((uint32_t)col0 >> 7) + tid);
+        else { o.w[0] = o.w[1] = o.w[2] = o.w[3] = 0u; }
+        sbits[tid * 4 + 0] = o.w[0]; sbits[tid * 4 + 1] = o.w[1];
+        sbits[tid * 4 + 2] = o.w[2]; sbits[tid * 4 + 3] = o.w[3];
+    }
+}
+
+// Stage A[k0 .. k0+15][col0 .. col0+511] of one segment, sign-flipped, row-major into LDS.
+template <int DTAB>
+__device__ __forceinline__ void lora_stage_slab(char *smem, const uint32_t *sbits, const LoraSeg &S, int32_t k0,
+                                                int32_t rank, int32_t col0, int32_t cols, uint32_t tid)
+{
+    if constexpr (DTAB == DT_BF16) {
+        const bool a_vec_ok = (cols % 8 == 0) && (((uintptr_t)S.A & 15u) == 0);
+        uint16_t *As = (uint16_t *)smem;
+        const RANDES_GLOBAL uint16_t *Ap = (const RANDES_GLOBAL uint16_t *)S.A;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int32_t kk = (int32_t)(tid >> 6) + 4 * p;      // 0..15 inside the slice
+            const int32_t k = k0 + kk;
+            const int32_t c8 = (int32_t)(tid & 63u) * 8;         // column inside the tile
+            const int32_t c = col0 + c8;
+            uint32_t w[4] = {0u, 0u, 0u, 0u};
+            if (k < rank && c < cols) {
+                if (a_vec_ok) {
+                    const u32x4 q = *(const RANDES_GLOBAL u32x4 *)(Ap + (int64_t)k * cols + c);
+                    w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (c + j < cols) w[j >> 1] |= (uint32_t)Ap[(int64_t)k * cols + c + j] << (16 * (j & 1));
+                }
+            }
+            const uint32_t bits = (sbits[c8 >> 5] >> (c8 & 31)) & 0xffu;
+            u32x4 q;
+            q.x = w[0] ^ ((((bits >> 0) & 1u) << 15) | (((bits >> 1) & 1u) << 31));
+            q.y = w[1] ^ ((((bits >> 2) & 1u) << 15) | (((bits >> 3) & 1u) << 31));
+            q.z = w[2] ^ ((((bits >> 4) & 1u) << 15) | (((bits >> 5) & 1u) << 31));
+            q.w = w[3] ^ ((((bits >> 6) & 1u) << 15) | (((bits >> 7) & 1u) << 31));
+            *(u32x4 *)(As + kk * AS_STRIDE + c8) = q;
+        }
+    } else {
+        uint32_t *As = (uint32_t *)smem;
+        const RANDES_GLOBAL uint32_t *Ap = (const RANDES_GLOBAL uint32_t *)S.A;
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            const int32_t kk = (int32_t)(tid >> 7) + 2 * p;      // 0..15
+            const int32_t k = k0 + kk;
+            const int32_t c4 = (int32_t)(tid & 127u) * 4;
+            const int32_t c = col0 + c4;
+            const uint32_t bits = (sbits[c4 >> 5] >> (c4 & 31)) & 0xfu;
+            u32x4 q = {0u, 0u, 0u, 0u};
+            if (k < rank) {
+                if (c < cols) q.x = Ap[(int64_t)k * cols + c];
+                if (c + 1 < cols) q.y = Ap[(int64_t)k * cols + c + 1];
+                if (c + 2 < cols) q.z = Ap[(int64_t)k * cols + c + 2];
+                if (c + 3 < cols) q.w = Ap[(int64_t)k * cols + c + 3];
+            }
+            q.x ^= ((bits >> 0) & 1u) << 31; q.y ^= ((bits >> 1) & 1u) << 31;
+            q.z ^= ((bits >> 2) & 1u) << 31; q.w ^= ((bits >> 3) & 1u) << 31;
+            *(u32x4 *)(As + kk * AS_STRIDE + c4) = q;
+        }
+    }
+}
+
+// bf16 factors: this lane's operand fragments (8 depth values of one column) of the wave's four
+// 32-column blocks, gathered from the staged slab.
+__device__ __forceinline__ void lora_gather(const char *smem, uint32_t wave, uint32_t half, uint32_t l32, u32x4 frag[4])
+{
+    const uint16_t *As = (const uint16_t *)smem;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        const uint32_t c = wave * 128u + (uint32_t)b * 32u + l32;
+        const uint16_t *col = As + (half * 8u) * AS_STRIDE + c;
+        frag[b].x = (uint32_t)col[0 * AS_STRIDE] | ((uint32_t)col[1 * AS_STRIDE] << 16);
+        frag[b].y = (uint32_t)col[2 * AS_STRIDE] | ((uint32_t)col[3 * AS_STRIDE] << 16);
+        frag[b].z = (uint32_t)col[4 * AS_STRIDE] | ((uint32_t)col[5 * AS_STRIDE] << 16);
+        frag[b].w = (uint32_t)col[6 * AS_STRIDE] | ((uint32_t)col[7 * AS_STRIDE] << 16);
+    }
+}
+
+// bf16 factors: this lane's 8 depth values B[my_row][k0 + 8*half ..] of one segment.
+__device__ __forceinline__ u32x4 lora_b_slice(const LoraSeg &S, int32_t my_row, bool row_ok, int32_t k0,
+                                              uint32_t half, int32_t rank)
+{
+    const bool b_vec_ok = (rank % 8 == 0) && (((uintptr_t)S.B & 15u) == 0);
+    const RANDES_GLOBAL uint16_t *Bp = (const RANDES_GLOBAL uint16_t *)S.B;
+    const int32_t kb = k0 + (int32_t)half * 8;
+    u32x4 q = {0u, 0u, 0u, 0u};
+    if (row_ok && kb < rank) {
+        if (b_vec_ok) {
+            q = *(const RANDES_GLOBAL u32x4 *)(Bp + (int64_t)my_row * rank + kb);
+        } else {
+            uint32_t aw[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (kb + j < rank) aw[j >> 1] |= (uint32_t)Bp[(int64_t)my_row * rank + kb + j] << (16 * (j & 1));
+            q.x = aw[0]; q.y = aw[1]; q.z = aw[2]; q.w = aw[3];
+        }
+    }
+    return q;
+}
+
+// binary32 factors: the 16-deep slice through the 32x32x2 MFMAs, right operand read from the slab.
+__device__ __forceinline__ void lora_mma_f32(const char *smem, const LoraSeg &S, int32_t my_row, bool row_ok,
+                                             int32_t k0, int32_t rank, uint32_t wave, uint32_t half, uint32_t l32,
+                                             f32x16 acc[4])
+{
+    const float *As = (const float *)smem;
+    const RANDES_GLOBAL float *Bp = (const RANDES_GLOBAL float *)S.B;
+#pragma unroll
+    for (int st = 0; st < KCH / 2; ++st) {
+        const int32_t kk = 2 * st + (int32_t)half;
+        const int32_t k = k0 + kk;
+        const float a = (row_ok && k < rank) ? Bp[(int64_t)my_row * rank + k] : 0.0f;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const uint32_t c = wave * 128u + (uint32_t)b * 32u + l32;
+            acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(As[kk * AS_STRIDE + c], a, acc[b], 0, 0, 0);
+        }
+    }
+}
+
+// RES > 0: every output matrix has at most RES depth slices (segments x ceil(rank / 16)); the
+// workgroup stages each slice once and, for bf16 factors, every wave keeps the gathered fragments
+// of all slices in registers, so that its row blocks only load their slices of B and multiply.
+// (binary32 factors: RES = 1 only, the single slab stays in LDS.)  RES = 0: any depth, slices
+// staged again for every row block.
+template <int DTAB, int DTO, int RES>
 __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t n_items, const LoraSeg *segs,
                                                   const uint32_t *coarse, int32_t rank, float scale)
 {
+    static_assert(RES >= 0 && RES <= LORA_RESIDENT_MAX && (DTAB == DT_BF16 || RES <= 1), "unsupported residency");
     constexpr int AT_BYTES = KCH * AS_STRIDE * (DTAB == DT_BF16 ? 2 : 4);
     constexpr int ST_BYTES = WAVES * LORA_TILE_M * ST_ROW_BYTES;
     __shared__ __attribute__((aligned(16))) char smem[AT_BYTES];       // the staged slab of A
@@ -77,15 +214,28 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
     const uint32_t lane = tid & 63u, half = lane >> 5, l32 = lane & 31u;
     const int32_t col0 = (int32_t)tx * LORA_TILE_N;
     const int32_t rows = it.rows, cols = it.cols;
-    const bool reuse_slab = (it.n_seg == 1) && (rank <= KCH);   // one staging serves every row block
-    u32x4 frag[4];   // bf16 factors: this lane's right-operand fragments of the four 32-column blocks
+    const int32_t slices_per_seg = (rank + KCH - 1) / KCH;
+    const int32_t n_slices = (int32_t)it.n_seg * slices_per_seg;    // <= RES when RES > 0 (host-checked)
+
+    constexpr int NF = RES > 0 ? RES : 1;
+    u32x4 frag[NF][4];   // bf16 factors: right-operand fragments per resident slice (RES = 0: of the current slice)
+    if constexpr (RES > 0) {
 #pragma unroll
-    for (int b = 0; b < 4; ++b) frag[b] = u32x4{0u, 0u, 0u, 0u};
+        for (int s = 0; s < RES; ++s) {
+            if (s < n_slices) {
+                const LoraSeg S = segs[it.seg_begin + (uint32_t)(s / slices_per_seg)];
+                lora_sign_bits(sbits, S, col0, tid);
+                __syncthreads();   // the previous slab is consumed; sbits are visible
+                lora_stage_slab<DTAB>(smem, sbits, S, (s % slices_per_seg) * KCH, rank, col0, cols, tid);
+                __syncthreads();
+                if constexpr (DTAB == DT_BF16) lora_gather(smem, wave, half, l32, frag[s]);
+            }
+        }
+    }
 
   for (int rt = 0; rt < LORA_ROW_TILES; ++rt) {
     const int32_t row0 = ((int32_t)ty * LORA_ROW_TILES + rt) * LORA_TILE_M;
     if (row0 >= rows) break;
-    const bool stage_now = !reuse_slab || rt == 0;
     const int32_t my_row = row0 + (int32_t)l32;              // left-operand row of this lane
     const bool row_ok = my_row < rows;
 
@@ -95,122 +245,44 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[b][v] = 0.0f;
 
-    for (uint32_t sg = 0; sg < it.n_seg; ++sg) {
-        const LoraSeg S = segs[it.seg_begin + sg];
-        // sign bits of this tile's 512 columns: four generator blocks (tiles start on multiples of 512)
-        if (stage_now && tid < LORA_TILE_N / 128) {
-            u32x4_t o;
-            if (S.flip) o = sign_block(S.key_lo, S.key_hi, S.layer_id, ((uint32_t)col0 >> 7) + tid);
-            else { o.w[0] = o.w[1] = o.w[2] = o.w[3] = 0u; }
-            sbits[tid * 4 + 0] = o.w[0]; sbits[tid * 4 + 1] = o.w[1];
-            sbits[tid * 4 + 2] = o.w[2]; sbits[tid * 4 + 3] = o.w[3];
+    if constexpr (RES > 0) {
+        if constexpr (DTAB == DT_BF16) {
+            u32x4 bsl[RES];   // all loads of the row block go out before the first multiply
+#pragma unroll
+            for (int s = 0; s < RES; ++s)
+                if (s < n_slices)
+                    bsl[s] = lora_b_slice(segs[it.seg_begin + (uint32_t)(s / slices_per_seg)], my_row, row_ok,
+                                          (s % slices_per_seg) * KCH, half, rank);
+#pragma unroll
+            for (int s = 0; s < RES; ++s)
+                if (s < n_slices) {
+                    const bf16x8 av = __builtin_bit_cast(bf16x8, bsl[s]);
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, frag[s][b]), av, acc[b], 0, 0, 0);
+                }
+        } else {
+            lora_mma_f32(smem, segs[it.seg_begin], my_row, row_ok, 0, rank, wave, half, l32, acc);
         }
-        const bool a_vec_ok = (cols % 8 == 0) && (((uintptr_t)S.A & 15u) == 0);
-        const bool b_vec_ok = (rank % 8 == 0) && (((uintptr_t)S.B & 15u) == 0);
-
-        for (int32_t k0 = 0; k0 < rank; k0 += KCH) {
-            // this lane's slice of B for the step: issued first so that it is in flight during the staging
-            uint32_t aw[4] = {0u, 0u, 0u, 0u};
-            if constexpr (DTAB == DT_BF16) {
-                const RANDES_GLOBAL uint16_t *Bp = (const RANDES_GLOBAL uint16_t *)S.B;
-                const int32_t kb = k0 + (int32_t)half * 8;
-                if (row_ok && kb < rank) {
-                    if (b_vec_ok) {
-                        const u32x4 q = *(const RANDES_GLOBAL u32x4 *)(Bp + (int64_t)my_row * rank + kb);
-                        aw[0] = q.x; aw[1] = q.y; aw[2] = q.z; aw[3] = q.w;
-                    } else {
+    } else {
+        for (uint32_t sg = 0; sg < it.n_seg; ++sg) {
+            const LoraSeg S = segs[it.seg_begin + sg];
+            lora_sign_bits(sbits, S, col0, tid);
+            for (int32_t k0 = 0; k0 < rank; k0 += KCH) {
+                // this lane's slice of B: issued first so that it is in flight during the staging
+                u32x4 bq = {0u, 0u, 0u, 0u};
+                if constexpr (DTAB == DT_BF16) bq = lora_b_slice(S, my_row, row_ok, k0, half, rank);
+                __syncthreads();   // the slab of the previous step is consumed; sbits are visible
+                lora_stage_slab<DTAB>(smem, sbits, S, k0, rank, col0, cols, tid);
+                __syncthreads();
+                if constexpr (DTAB == DT_BF16) {
+                    lora_gather(smem, wave, half, l32, frag[0]);
+                    const bf16x8 av = __builtin_bit_cast(bf16x8, bq);
 #pragma unroll
-                        for (int j = 0; j < 8; ++j)
-                            if (kb + j < rank) aw[j >> 1] |= (uint32_t)Bp[(int64_t)my_row * rank + kb + j] << (16 * (j & 1));
-                    }
-                }
-            }
-            if (stage_now) {
-            __syncthreads();   // the slab of the previous step is consumed; sbits are visible
-            // ---- stage A[k0 .. k0+15][col0 .. col0+511], sign-flipped ----
-            if constexpr (DTAB == DT_BF16) {
-                uint16_t *As = (uint16_t *)smem;
-                const RANDES_GLOBAL uint16_t *Ap = (const RANDES_GLOBAL uint16_t *)S.A;
-#pragma unroll
-                for (int p = 0; p < 4; ++p) {
-                    const int32_t kk = (int32_t)(tid >> 6) + 4 * p;      // 0..15 inside the slice
-                    const int32_t k = k0 + kk;
-                    const int32_t c8 = (int32_t)(tid & 63u) * 8;         // column inside the tile
-                    const int32_t c = col0 + c8;
-                    uint32_t w[4] = {0u, 0u, 0u, 0u};
-                    if (k < rank && c < cols) {
-                        if (a_vec_ok) {
-                            const u32x4 q = *(const RANDES_GLOBAL u32x4 *)(Ap + (int64_t)k * cols + c);
-                            w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
-                        } else {
-#pragma unroll
-                            for (int j = 0; j < 8; ++j)
-                                if (c + j < cols) w[j >> 1] |= (uint32_t)Ap[(int64_t)k * cols + c + j] << (16 * (j & 1));
-                        }
-                    }
-                    const uint32_t bits = (sbits[c8 >> 5] >> (c8 & 31)) & 0xffu;
-                    u32x4 q;
-                    q.x = w[0] ^ ((((bits >> 0) & 1u) << 15) | (((bits >> 1) & 1u) << 31));
-                    q.y = w[1] ^ ((((bits >> 2) & 1u) << 15) | (((bits >> 3) & 1u) << 31));
-                    q.z = w[2] ^ ((((bits >> 4) & 1u) << 15) | (((bits >> 5) & 1u) << 31));
-                    q.w = w[3] ^ ((((bits >> 6) & 1u) << 15) | (((bits >> 7) & 1u) << 31));
-                    *(u32x4 *)(As + kk * AS_STRIDE + c8) = q;
-                }
-            } else {
-                uint32_t *As = (uint32_t *)smem;
-                const RANDES_GLOBAL uint32_t *Ap = (const RANDES_GLOBAL uint32_t *)S.A;
-#pragma unroll
-                for (int p = 0; p < 8; ++p) {
-                    const int32_t kk = (int32_t)(tid >> 7) + 2 * p;      // 0..15
-                    const int32_t k = k0 + kk;
-                    const int32_t c4 = (int32_t)(tid & 127u) * 4;
-                    const int32_t c = col0 + c4;
-                    const uint32_t bits = (sbits[c4 >> 5] >> (c4 & 31)) & 0xfu;
-                    u32x4 q = {0u, 0u, 0u, 0u};
-                    if (k < rank) {
-                        if (c < cols) q.x = Ap[(int64_t)k * cols + c];
-                        if (c + 1 < cols) q.y = Ap[(int64_t)k * cols + c + 1];
-                        if (c + 2 < cols) q.z = Ap[(int64_t)k * cols + c + 2];
-                        if (c + 3 < cols) q.w = Ap[(int64_t)k * cols + c + 3];
-                    }
-                    q.x ^= ((bits >> 0) & 1u) << 31; q.y ^= ((bits >> 1) & 1u) << 31;
-                    q.z ^= ((bits >> 2) & 1u) << 31; q.w ^= ((bits >> 3) & 1u) << 31;
-                    *(u32x4 *)(As + kk * AS_STRIDE + c4) = q;
-                }
-            }
-            __syncthreads();
-            }
-            // ---- multiply ----
-            if constexpr (DTAB == DT_BF16) {
-                const uint16_t *As = (const uint16_t *)smem;
-                u32x4 aq; aq.x = aw[0]; aq.y = aw[1]; aq.z = aw[2]; aq.w = aw[3];
-                const bf16x8 av = __builtin_bit_cast(bf16x8, aq);
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    if (stage_now) {   // with a reused slab the gathered fragments serve every row block
-                        const uint32_t c = wave * 128u + (uint32_t)b * 32u + l32;
-                        const uint16_t *col = As + (half * 8u) * AS_STRIDE + c;
-                        frag[b].x = (uint32_t)col[0 * AS_STRIDE] | ((uint32_t)col[1 * AS_STRIDE] << 16);
-                        frag[b].y = (uint32_t)col[2 * AS_STRIDE] | ((uint32_t)col[3 * AS_STRIDE] << 16);
-                        frag[b].z = (uint32_t)col[4 * AS_STRIDE] | ((uint32_t)col[5 * AS_STRIDE] << 16);
-                        frag[b].w = (uint32_t)col[6 * AS_STRIDE] | ((uint32_t)col[7 * AS_STRIDE] << 16);
-                    }
-                    const u32x4 bq = frag[b];
-                    acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bq), av, acc[b], 0, 0, 0);
-                }
-            } else {
-                const float *As = (const float *)smem;
-                const RANDES_GLOBAL float *Bp = (const RANDES_GLOBAL float *)S.B;
-#pragma unroll
-                for (int st = 0; st < KCH / 2; ++st) {
-                    const int32_t kk = 2 * st + (int32_t)half;
-                    const int32_t k = k0 + kk;
-                    const float a = (row_ok && k < rank) ? Bp[(int64_t)my_row * rank + k] : 0.0f;
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        const uint32_t c = wave * 128u + (uint32_t)b * 32u + l32;
-                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(As[kk * AS_STRIDE + c], a, acc[b], 0, 0, 0);
-                    }
+                    for (int b = 0; b < 4; ++b)
+                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, frag[0][b]), av, acc[b], 0, 0, 0);
+                } else {
+                    lora_mma_f32(smem, S, my_row, row_ok, k0, rank, wave, half, l32, acc);
                 }
             }
         }
@@ -294,18 +366,35 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
 }
 
 hipError_t launch_lora(const LoraItem *items_dev, int32_t n_items, const LoraSeg *segs_dev, const uint32_t *coarse_dev,
-                       uint32_t n_tiles, int32_t rank, float scale, int dt_ab, int dt_out, hipStream_t s)
+                       uint32_t n_tiles, int32_t max_seg, int32_t rank, float scale, int dt_ab, int dt_out, hipStream_t s)
 {
     if (n_tiles == 0) return hipSuccess;
     const dim3 grid(n_tiles), block(WG);
-    if (dt_ab == DT_BF16 && dt_out == DT_BF16)
-        hipLaunchKernelGGL((lora_kernel<DT_BF16, DT_BF16>), grid, block, 0, s, items_dev, n_items, segs_dev, coarse_dev, rank, scale);
-    else if (dt_ab == DT_BF16)
-        hipLaunchKernelGGL((lora_kernel<DT_BF16, DT_F32>), grid, block, 0, s, items_dev, n_items, segs_dev, coarse_dev, rank, scale);
-    else if (dt_out == DT_BF16)
-        hipLaunchKernelGGL((lora_kernel<DT_F32, DT_BF16>), grid, block, 0, s, items_dev, n_items, segs_dev, coarse_dev, rank, scale);
-    else
-        hipLaunchKernelGGL((lora_kernel<DT_F32, DT_F32>), grid, block, 0, s, items_dev, n_items, segs_dev, coarse_dev, rank, scale);
+    const int64_t slices = (int64_t)max_seg * ((rank + KCH - 1) / KCH);   // depth slices of the deepest matrix
+#define RANDES_LORA(DA, DO, RES) hipLaunchKernelGGL((lora_kernel<DA, DO, RES>), grid, block, 0, s, items_dev, n_items, \
+                                                    segs_dev, coarse_dev, rank, scale)
+    if (dt_ab == DT_BF16) {
+        // fragments of 1, up to 4 or up to 8 slices in registers (92 / ~150 / 245 registers per lane)
+        const int res = slices <= 1 ? 1 : (slices <= 4 ? 4 : (slices <= LORA_RESIDENT_MAX ? LORA_RESIDENT_MAX : 0));
+        if (dt_out == DT_BF16) {
+            if (res == 1) RANDES_LORA(DT_BF16, DT_BF16, 1);
+            else if (res == 4) RANDES_LORA(DT_BF16, DT_BF16, 4);
+            else if (res == LORA_RESIDENT_MAX) RANDES_LORA(DT_BF16, DT_BF16, LORA_RESIDENT_MAX);
+            else RANDES_LORA(DT_BF16, DT_BF16, 0);
+        } else {
+            if (res == 1) RANDES_LORA(DT_BF16, DT_F32, 1);
+            else if (res == 4) RANDES_LORA(DT_BF16, DT_F32, 4);
+            else if (res == LORA_RESIDENT_MAX) RANDES_LORA(DT_BF16, DT_F32, LORA_RESIDENT_MAX);
+            else RANDES_LORA(DT_BF16, DT_F32, 0);
+        }
+    } else {
+        if (dt_out == DT_BF16) {
+            if (slices <= 1) RANDES_LORA(DT_F32, DT_BF16, 1); else RANDES_LORA(DT_F32, DT_BF16, 0);
+        } else {
+            if (slices <= 1) RANDES_LORA(DT_F32, DT_F32, 1); else RANDES_LORA(DT_F32, DT_F32, 0);
+        }
+    }
+#undef RANDES_LORA
     return hipGetLastError();
 }
 
