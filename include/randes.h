@@ -136,6 +136,25 @@ int randes_retrieve(const randes_layer *layers, int32_t n_layers,
                     uint64_t seed, float lambda,
                     void *const *out, randes_dtype out_dtype, void *hip_stream);
 
+/* retrieve for several models in one pass over the superposition (the retrieval of Sec. 4 applied
+ * n_requests times; "retrieve(Theta*, i)" of the problem setup for a batch of i): for request q,
+ *   outs[q][t_q][r][c] = fma(lambdas[q], (-1)^{s(seeds[q], l, c)} * merged[l][r][c], base[t_q][r][c]),  t_q = src_q(l)
+ * every output stack bit-identical to what randes_retrieve gives for (seeds[q], lambdas[q]).
+ * When merged, base and outs share one dtype and every layer is 16-byte aligned with cols a
+ * multiple of 4 (f32) / 8 (bf16), requests are served 8, 4 or 2 at a time by a kernel that reads
+ * each merged tile once for all of them (2 + 4 q bytes per element and q requests in bf16 instead
+ * of 6 q); otherwise, and for a request left over, the call runs randes_retrieve per request.
+ *   seeds, lambdas   host arrays of n_requests
+ *   outs             host array of n_requests * n_layers device pointers; outs[q * n_layers + l] =
+ *                    request q's layer l.  Output stacks must not overlap each other, merged or base
+ *                    (unlike randes_retrieve, base is read by every request of a pass).
+ * Errors: RANDES_EINVAL (also n_requests < 1, NaN / Inf lambda, overlapping outputs), RANDES_EHIP. */
+int randes_retrieve_many(const randes_layer *layers, int32_t n_layers,
+                         const void *const *merged, randes_dtype merged_dtype,
+                         const void *const *base, randes_dtype base_dtype,
+                         int32_t n_requests, const uint64_t *seeds, const float *lambdas,
+                         void *const *outs, randes_dtype out_dtype, void *hip_stream);
+
 /* Hot swap (Sec. "Model Hot Swapping"): add (remove = 0) or remove (remove != 0)
  * one model in place, without touching the others:
  *   merged[l][r][c] <- merged[l][r][c] +/- (-1)^{s(seed, l, c)} * delta[src(l)][r][c]

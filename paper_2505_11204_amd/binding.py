@@ -23,7 +23,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "librandes.so")
 
 EXPORTS = ["randes_layer_perm", "randes_source_table", "randes_sign_mask", "randes_merge", "randes_merge_weights",
-           "randes_retrieve", "randes_update", "randes_delta_stats", "randes_lora_materialize",
+           "randes_retrieve", "randes_retrieve_many", "randes_update", "randes_delta_stats", "randes_lora_materialize",
            "randes_lora_materialize_batched", "randes_lora_merge", "randes_strerror", "randes_shutdown",
            "randes_set_tile_rows", "randes_set_tile_cols",
            "randes_probe_stream"]
@@ -60,6 +60,8 @@ def lib():
     L.randes_merge_weights.argtypes = [vp, i32, vp, vp, i32, vp, ctypes.c_int, vp, ctypes.c_int, vp]
     L.randes_retrieve.argtypes = [vp, i32, vp, ctypes.c_int, vp, ctypes.c_int, u64, ctypes.c_float,
                                   vp, ctypes.c_int, vp]
+    L.randes_retrieve_many.argtypes = [vp, i32, vp, ctypes.c_int, vp, ctypes.c_int, i32, vp, vp,
+                                       vp, ctypes.c_int, vp]
     L.randes_update.argtypes = [vp, i32, vp, ctypes.c_int, vp, ctypes.c_int, u64, i32, vp]
     L.randes_delta_stats.argtypes = [vp, i32, vp, u64, vp, u64, ctypes.c_int, vp, vp]
     L.randes_lora_materialize.argtypes = [vp, vp, i64, i64, i32, ctypes.c_float, ctypes.c_int, vp,
@@ -244,6 +246,34 @@ def retrieve(layers, merged, base, seed, lam, out=None, out_dtype=None, stream=N
     _check(lib().randes_retrieve(lt.array, lt.n, mt.array, mt.code, bt.array, bt.code, _u64(seed),
                                  ctypes.c_float(lam), ot.array, ot.code, _stream(stream)))
     return out
+
+
+def retrieve_many(layers, merged, base, seeds, lams, outs=None, out_dtype=None, stream=None):
+    """retrieve several models in one pass: returns one list of layers per request
+    (or the PtrTable passed as ``outs``, which then holds request q's layer l at q * n_layers + l)."""
+    lt = _layer_table(layers)
+    mt = _ptr_table(merged, lt)
+    bt = _ptr_table(base, lt)
+    n = len(seeds)
+    if len(lams) != n:
+        raise ValueError("%d lambdas for %d seeds" % (len(lams), n))
+    result = outs
+    if outs is None:
+        od = bt.dtype if out_dtype is None else out_dtype
+        result = [alloc_like_layers(lt, od, bt.tensors[0].device) for _ in range(n)]
+        outs = result
+    if not isinstance(outs, PtrTable):
+        flat = [t for per_request in outs for t in per_request]
+        if not flat:
+            raise ValueError("no requests given")
+        outs = PtrTable(flat, lt)
+    if len(outs.tensors) != n * lt.n:
+        raise ValueError("outs holds %d tensors, expected %d" % (len(outs.tensors), n * lt.n))
+    sd = (ctypes.c_uint64 * max(n, 1))(*[_u64(s) for s in seeds])
+    la = (ctypes.c_float * max(n, 1))(*[float(x) for x in lams])
+    _check(lib().randes_retrieve_many(lt.array, lt.n, mt.array, mt.code, bt.array, bt.code, n, sd, la,
+                                      outs.array, outs.code, _stream(stream)))
+    return result
 
 
 def update(layers, merged, delta, seed, remove=False, stream=None):

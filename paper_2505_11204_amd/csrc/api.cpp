@@ -397,6 +397,132 @@ int randes_retrieve(const randes_layer *layers, int32_t n_layers,
     return RANDES_OK;
 }
 
+}  // extern "C"
+
+namespace {
+
+// q = 2, 4 or 8 requests in one pass; every layer already known to take the vector path.
+int retrieve_many_pass(const randes_layer *layers, int32_t n_layers, const void *const *merged,
+                       const void *const *base, int32_t q, const uint64_t *seeds, const float *lambdas,
+                       void *const *outs, int dtype, void *hip_stream)
+{
+    int dev, rc;
+    if ((rc = current_device(&dev))) return rc;
+    std::lock_guard<std::mutex> lock(g_mu);
+    std::string key, why;
+    const int32_t head[5] = { PLAN_RETRIEVE_MANY, n_layers, dtype, q, g_max_wx_shift };
+    append(&key, head, sizeof(head));
+    append(&key, layers, sizeof(randes_layer) * (size_t)n_layers);
+    append(&key, merged, sizeof(void *) * (size_t)n_layers);
+    append(&key, base, sizeof(void *) * (size_t)n_layers);
+    append(&key, outs, sizeof(void *) * (size_t)n_layers * (size_t)q);
+    append(&key, seeds, sizeof(uint64_t) * (size_t)q);
+
+    CachedPlan *cp = lookup(key, dev);
+    if (!cp) {
+        HostPlan hp;
+        std::vector<std::vector<int32_t>> src((size_t)q);
+        for (int32_t i = 0; i < q; ++i) {
+            if ((rc = build_source_table(layers, n_layers, seeds[i], &src[(size_t)i], &why))) return fail(rc, why);
+            hp.keys.push_back((uint32_t)(seeds[i] & 0xffffffffu));
+            hp.keys.push_back((uint32_t)(seeds[i] >> 32));
+        }
+        const int vec = retrieve_vec(dtype, dtype);
+        std::vector<const void *> ptrs((size_t)(2 * q));
+        for (int32_t l = 0; l < n_layers; ++l) {
+            LayerDev d{};
+            d.a = merged[l];
+            d.rows = (int32_t)layers[l].rows;
+            d.cols = (int32_t)layers[l].cols;
+            d.layer_id = (uint32_t)l;
+            d.flip = (layers[l].flags & RANDES_FLIP) ? 1u : 0u;
+            for (int32_t i = 0; i < q; ++i) {
+                const int32_t t = src[(size_t)i][(size_t)l];
+                ptrs[(size_t)i] = base[t];
+                ptrs[(size_t)(q + i)] = outs[(size_t)i * n_layers + t];
+            }
+            if ((rc = place(&hp, d, ptrs.data(), 2 * q, true, vec, retrieve_many_rows(q)))) return rc;
+        }
+        CachedPlan fresh;
+        fresh.key = key;
+        fresh.device = dev;
+        if ((rc = upload(hp, q, &fresh))) return rc;
+        cp = insert_plan(std::move(fresh));
+    }
+    StreamArgs av = cp->vec;
+    for (int32_t i = 0; i < q; ++i) av.lambdas[i] = lambdas[i];
+    hipError_t e = launch_retrieve_many(av, dtype, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail(e, "retrieve (several models) launch");
+    return RANDES_OK;
+}
+
+// True if any two of the spans overlap.
+bool any_overlap(std::vector<Span> spans)
+{
+    std::sort(spans.begin(), spans.end(), [](const Span &a, const Span &b) { return a.lo < b.lo; });
+    uintptr_t hi = 0;
+    for (const Span &s : spans) {
+        if (s.lo < hi) return true;
+        hi = std::max(hi, s.hi);
+    }
+    return false;
+}
+
+}  // namespace
+
+extern "C" {
+
+int randes_retrieve_many(const randes_layer *layers, int32_t n_layers,
+                         const void *const *merged, randes_dtype merged_dtype,
+                         const void *const *base, randes_dtype base_dtype,
+                         int32_t n_requests, const uint64_t *seeds, const float *lambdas,
+                         void *const *outs, randes_dtype out_dtype, void *hip_stream)
+{
+    std::string why;
+    int rc = validate_layers(layers, n_layers, &why);
+    if (rc) return fail(rc, why);
+    if (!merged || !base || !outs || !seeds || !lambdas) return fail(RANDES_EINVAL, "merged, base, outs, seeds or lambdas is NULL");
+    if (n_requests < 1) return fail(RANDES_EINVAL, "n_requests < 1");
+    if (!dtype_ok(merged_dtype) || !dtype_ok(base_dtype) || !dtype_ok(out_dtype)) return fail(RANDES_EINVAL, "unknown dtype");
+    for (int32_t q = 0; q < n_requests; ++q)
+        if (!std::isfinite(lambdas[q])) return fail(RANDES_EINVAL, "lambda is not finite");
+    const int vec = retrieve_vec(merged_dtype, base_dtype);
+    bool vector_ok = merged_dtype == base_dtype && base_dtype == out_dtype;
+    std::vector<Span> out_spans, both;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        if (!merged[l] || !base[l] || !elem_aligned(merged[l], merged_dtype) || !elem_aligned(base[l], base_dtype))
+            return fail(RANDES_EINVAL, "NULL or misaligned layer pointer");
+        const size_t n = (size_t)layers[l].rows * (size_t)layers[l].cols;
+        both.push_back({ (uintptr_t)merged[l], (uintptr_t)merged[l] + n * elem_bytes(merged_dtype), 1 });
+        both.push_back({ (uintptr_t)base[l], (uintptr_t)base[l] + n * elem_bytes(base_dtype), 1 });
+        vector_ok = vector_ok && (layers[l].cols % vec) == 0 && aligned16(merged[l]) && aligned16(base[l]);
+        for (int32_t q = 0; q < n_requests; ++q) {
+            void *o = outs[(size_t)q * n_layers + l];
+            if (!o || !elem_aligned(o, out_dtype)) return fail(RANDES_EINVAL, "NULL or misaligned output pointer");
+            out_spans.push_back({ (uintptr_t)o, (uintptr_t)o + n * elem_bytes(out_dtype), 0 });
+            both.push_back(out_spans.back());
+            vector_ok = vector_ok && aligned16(o);
+        }
+    }
+    if (any_overlap(out_spans)) return fail(RANDES_EINVAL, "output stacks overlap each other");
+    if (overlap(both)) return fail(RANDES_EINVAL, "an output overlaps merged or base");
+    // geometry limits are the single retrieval's; let it report them
+    int32_t q0 = 0;
+    while (q0 < n_requests) {
+        const int32_t left = n_requests - q0;
+        const int32_t q = !vector_ok ? 1 : (left >= 8 ? 8 : (left >= 4 ? 4 : (left >= 2 ? 2 : 1)));
+        if (q == 1)
+            rc = randes_retrieve(layers, n_layers, merged, merged_dtype, base, base_dtype, seeds[q0], lambdas[q0],
+                                 outs + (size_t)q0 * n_layers, out_dtype, hip_stream);
+        else
+            rc = retrieve_many_pass(layers, n_layers, merged, base, q, seeds + q0, lambdas + q0,
+                                    outs + (size_t)q0 * n_layers, (int)merged_dtype, hip_stream);
+        if (rc) return rc;
+        q0 += q;
+    }
+    return RANDES_OK;
+}
+
 int randes_update(const randes_layer *layers, int32_t n_layers,
                   void *const *merged, randes_dtype merged_dtype,
                   const void *const *delta, randes_dtype delta_dtype,

@@ -466,6 +466,81 @@ __global__ void __launch_bounds__(WG) retrieve_kernel(const StreamArgs A)
     two_input_bursts<DTM, DTB, DTO, VEC, true>(A, t, (gcptr)t.L.a, (gcptr)t.L.b, (gptr)t.L.dst, sbits);
 }
 
+// ---------------------------------------------------------------------------
+// Several retrievals in one pass: for Q models at once,
+//   out_q[t_q] = fma(lambda_q, D_q-flipped merged[l], base[t_q]),  t_q = src_q(l),
+// each bit-identical to the single retrieval.  The merged tile is read once for all Q models
+// (the base tiles are not shared: under model q's permutation slot l maps to its own layer t_q).
+// The source table holds, per slot layer, the Q base pointers followed by the Q output pointers.
+// Mirror image of the merge: 1 + Q read streams, Q write streams; all loads of the burst, the
+// sign bits while they fly, the arithmetic in place over the base registers, then all stores.
+// ---------------------------------------------------------------------------
+template <int DT, int VEC, int QT>
+__global__ void __launch_bounds__(WG) retrieve_many_kernel(const StreamArgs A)
+{
+    constexpr int NW = NumWords<DT, VEC>::value;
+    static_assert(NW == OutWords<DT, VEC>::value, "results replace the base registers word for word");
+    constexpr uint32_t EB = (DT == DT_F32) ? 4 : 2;
+    constexpr int R = retrieve_many_rows(QT);
+    extern __shared__ uint32_t sbits[];
+    const Tile t = locate<VEC>(A);
+    if (!t.valid) return;   // whole workgroup, before any barrier
+    const uint32_t cols = (uint32_t)t.L.cols;
+    const size_t tile_off = (size_t)t.row0 * cols * EB;
+    const gcptr pm = (gcptr)t.L.a + tile_off;
+    gcptr pb[QT];
+    gptr po[QT];
+#pragma unroll
+    for (int q = 0; q < QT; ++q) {
+        pb[q] = (gcptr)A.srcs[(size_t)t.layer_slot * (2 * QT) + q] + tile_off;
+        po[q] = (gptr)A.srcs[(size_t)t.layer_slot * (2 * QT) + QT + q] + tile_off;
+    }
+    const uint32_t off = (t.wy * cols + t.col) * EB, step = t.WY * cols * EB;   // bytes inside the tile, below 2^32
+    const uint32_t r = t.row0 + t.wy;
+    uint32_t rm[R][NW], ry[R][QT][NW];
+    if (t.active) {
+#pragma unroll
+        for (int u = 0; u < R; ++u)
+            if (r + t.WY * u < t.row_end) {
+                load_raw<DT, VEC>(pm + (off + u * step), rm[u]);
+#pragma unroll
+                for (int q = 0; q < QT; ++q) load_raw<DT, VEC>(pb[q] + (off + u * step), ry[u][q]);
+            }
+    }
+    const uint32_t nblk = stage_sign_bits(sbits, t, A.keys, (uint32_t)QT, 0u, 0u);
+    lds_barrier();
+    if (!t.active) return;
+    uint32_t bits[QT];
+#pragma unroll
+    for (int q = 0; q < QT; ++q) bits[q] = lane_bits_from_lds<VEC>(sbits, t, nblk, (uint32_t)q);
+    // The plan gives a wave at most R rows of a tile, so this one burst is all its work.
+#pragma unroll
+    for (int u = 0; u < R; ++u)
+        if (r + t.WY * u < t.row_end) {
+            float x[VEC];
+            widen<DT, VEC>(rm[u], x);
+#pragma unroll
+            for (int q = 0; q < QT; ++q) {
+                float y[VEC], o[VEC];
+                widen<DT, VEC>(ry[u][q], y);
+                const float lambda = A.lambdas[q];
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    const float xs = u2f(f2u(x[j]) ^ ((bits[q] << (31 - j)) & 0x80000000u));
+                    o[j] = __builtin_fmaf(lambda, xs, y[j]);
+                }
+                pack_out<DT, VEC>(o, ry[u][q]);
+            }
+        }
+    load_store_fence();
+#pragma unroll
+    for (int u = 0; u < R; ++u)
+        if (r + t.WY * u < t.row_end) {
+#pragma unroll
+            for (int q = 0; q < QT; ++q) store_words<DT, VEC>(po[q] + (off + u * step), ry[u][q]);
+        }
+}
+
 // hot swap: the flipped stream is the delta; the other input and the output are merged[l].
 template <int DTM, int DTD, int VEC>
 __global__ void __launch_bounds__(WG) update_kernel(const StreamArgs A)
@@ -750,6 +825,28 @@ hipError_t launch_retrieve(const StreamArgs &a, int vec, int dt_merged, int dt_b
     case 6: return retrieve_dispatch<DT_BF16, DT_F32, 8>(a, dt_out, s);
     default: return retrieve_dispatch<DT_BF16, DT_BF16, 8>(a, dt_out, s);
     }
+}
+
+template <int DT, int VEC>
+static hipError_t retrieve_many_dispatch(const StreamArgs &a, hipStream_t s)
+{
+    const dim3 grid(xcd_grid(a.n_tiles)), block(WG);
+    const size_t lds = sign_bits_lds_bytes(a.n_tasks, VEC);
+    switch (a.n_tasks) {
+    case 2: hipLaunchKernelGGL((retrieve_many_kernel<DT, VEC, 2>), grid, block, lds, s, a); break;
+    case 4: hipLaunchKernelGGL((retrieve_many_kernel<DT, VEC, 4>), grid, block, lds, s, a); break;
+    case 8: hipLaunchKernelGGL((retrieve_many_kernel<DT, VEC, 8>), grid, block, lds, s, a); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// n_tasks of the arguments = models per pass (2, 4 or 8); one storage type for all three stacks.
+hipError_t launch_retrieve_many(const StreamArgs &a, int dt, hipStream_t s)
+{
+    if (a.n_tiles == 0) return hipSuccess;
+    if (dt == DT_F32) return retrieve_many_dispatch<DT_F32, 4>(a, s);
+    return retrieve_many_dispatch<DT_BF16, 8>(a, s);
 }
 
 template <int DTM, int DTD, int VEC>

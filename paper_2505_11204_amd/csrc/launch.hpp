@@ -15,6 +15,8 @@ hipError_t launch_merge(const StreamArgs &a, int vec, int dt_in, int dt_out, hip
 hipError_t launch_merge_weights(const StreamArgs &a, int vec, int dt_in, int dt_out, hipStream_t s);
 hipError_t launch_retrieve(const StreamArgs &a, int vec, int dt_merged, int dt_base, int dt_out, hipStream_t s);
 hipError_t launch_update(const StreamArgs &a, int vec, int dt_merged, int dt_delta, hipStream_t s);
+// a.n_tasks models (2, 4 or 8) retrieved in one pass; vector path only, one storage type.
+hipError_t launch_retrieve_many(const StreamArgs &a, int dt, hipStream_t s);
 // stats: per-workgroup partial triples into a.partials, then stats_finalize sums n_partials of them
 // in a fixed order into out3 = { <a',b'>, <a',a'>, <b',b'> }.
 hipError_t launch_stats(const StreamArgs &a, int vec, int dt, hipStream_t s);
@@ -51,6 +53,10 @@ int update_vec(int dt_merged, int dt_delta);
 int stats_vec(int dt);
 int merge_burst_rows();
 int merge_weights_burst_rows();
+// Rows per wave of the kernel that retrieves q models in one pass: 4 * (1 + 8) = 36 or
+// 8 * (1 + q) <= 40 sixteen-byte loads in flight per lane.
+constexpr int retrieve_many_rows(int q) { return q >= 8 ? 4 : 8; }
+
 // Two-input kernels (retrieve, update, stats): rows per burst so that about 32 sixteen-byte loads are
 // in flight per lane: 16 rows when both streams fit 16 bytes per lane, fewer when a stream is wider.
 // words_x / words_y = 32-bit words per lane and row of the two streams.

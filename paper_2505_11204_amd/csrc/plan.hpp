@@ -30,7 +30,7 @@ struct LayerDev {
 // What a streaming kernel receives by value.
 struct StreamArgs {
     const LayerDev *layers;       // n_layers
-    const void *const *srcs;      // merge only: [n_layers][n_tasks] source pointers
+    const void *const *srcs;      // merge: [n_layers][n_tasks] source pointers (several retrievals: base, then output pointers)
     const uint32_t *tile_begin;   // n_layers + 1 prefix sums of tiles
     const uint32_t *coarse;       // coarse[i] = layer that holds tile 1024 * i (one extra entry at the end)
     const uint32_t *keys;         // merge only: [n_tasks][2] = (seed low, seed high)
@@ -39,6 +39,7 @@ struct StreamArgs {
     uint32_t n_tiles;
     uint32_t key_lo, key_hi;      // retrieve / update: the one model's seed
     float lambda;                 // retrieve
+    float lambdas[8];             // several retrievals in one pass: one scale per model
     uint32_t negate;              // update: 1 removes the model
     uint32_t key2_lo, key2_hi;    // stats: the second model's seed
     double *partials;             // stats: one triple per workgroup
@@ -60,7 +61,8 @@ struct HostPlan {
     size_t extra_bytes = 0;   // scratch appended to the device tables (stats: per-workgroup partials)
 };
 
-enum PlanKind { PLAN_MERGE = 1, PLAN_RETRIEVE = 2, PLAN_UPDATE = 3, PLAN_MERGE_WEIGHTS = 4, PLAN_STATS = 5 };
+enum PlanKind { PLAN_MERGE = 1, PLAN_RETRIEVE = 2, PLAN_UPDATE = 3, PLAN_MERGE_WEIGHTS = 4, PLAN_STATS = 5,
+                PLAN_RETRIEVE_MANY = 6 };
 
 int validate_layers(const randes_layer *layers, int32_t n_layers, std::string *why);
 

@@ -444,3 +444,80 @@ def test_extreme_shapes(rows, cols):
     out = rb.retrieve(layers, m, to_gpu(base), 6, 0.5)
     oo = oracle.retrieve(layers, om, np_lists(base), 6, 0.5, 1, 1, 1, n_threads=8)
     compare(out[0], oo[0], "extreme retrieve")
+
+
+def aligned_stack():
+    """Every layer on the vector path (cols a multiple of 8, 256-byte aligned allocations):
+    ragged row tails, partly filled column tiles, two shuffle groups, a shifted group, singletons."""
+    return [
+        Layer(130, 1032, 0, SRSF), Layer(70, 520, 1, SRSF), Layer(130, 1032, 0, SRSF),
+        Layer(257, 136, -1, FLIP), Layer(70, 520, 1, SRSF), Layer(130, 1032, 0, SRSF),
+        Layer(1, 3000, -1, FLIP), Layer(33, 2048, 2, FLIP | SHIFT), Layer(33, 2048, 2, FLIP | SHIFT),
+        Layer(33, 2048, 2, FLIP | SHIFT), Layer(64, 4104, -1, 0), Layer(9, 8, -1, FLIP),
+    ]
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("n_req", [1, 2, 3, 5, 8, 11, 15])
+def test_retrieve_many_equals_single_retrievals_and_the_oracle(dt, n_req):
+    # 15 = 8 + 4 + 2 + 1 exercises every pass size; seeds repeat (several requests for one model)
+    stack = aligned_stack()
+    layers = layers_of(stack)
+    K = 4
+    seeds = [900 + i for i in range(K)]
+    base, deltas = cpu_inputs(stack, K, dt)
+    g_merged = rb.merge(layers, [to_gpu(d) for d in deltas], seeds)
+    o_merged = oracle.merge(layers, [np_lists(d) for d in deltas], seeds, CODE[dt], CODE[dt], n_threads=8)
+    g_base = to_gpu(base)
+    req_seeds = [seeds[(3 * q + 1) % K] for q in range(n_req)]
+    lams = [0.25 + 0.125 * q for q in range(n_req)]
+    outs = rb.retrieve_many(layers, g_merged, g_base, req_seeds, lams)
+    assert len(outs) == n_req
+    for q in range(n_req):
+        single = rb.retrieve(layers, g_merged, g_base, req_seeds[q], lams[q])
+        want = oracle.retrieve(layers, o_merged, np_lists(base), req_seeds[q], lams[q],
+                               CODE[dt], CODE[dt], CODE[dt], n_threads=8)
+        for l in range(len(stack)):
+            assert torch.equal(outs[q][l].view(torch.int16 if dt == "bf16" else torch.int32),
+                               single[l].view(torch.int16 if dt == "bf16" else torch.int32))
+            compare(outs[q][l], want[l], "request %d layer %d" % (q, l))
+
+
+@pytest.mark.parametrize("case", ["ragged", "mixed_dtypes", "launch_shape"])
+def test_retrieve_many_other_paths(case):
+    # layers off the vector path, or stacks of different dtypes, are served request by request;
+    # the launch-shape knob must not change the result of the one-pass kernel
+    stack = ragged_stack() if case == "ragged" else aligned_stack()
+    layers = layers_of(stack)
+    K, dt = 3, "bf16"
+    seeds = [77, 78, 79]
+    base, deltas = cpu_inputs(stack, K, dt)
+    d_merged = "f32" if case == "mixed_dtypes" else dt
+    g_merged = rb.merge(layers, [to_gpu(d) for d in deltas], seeds, merged_dtype=TD[d_merged])
+    o_merged = oracle.merge(layers, [np_lists(d) for d in deltas], seeds, CODE[dt], CODE[d_merged], n_threads=8)
+    g_base = to_gpu(base)
+    if case == "launch_shape":
+        rb.set_tile_cols(1)
+    req = [79, 77, 78, 77]
+    lams = [1.0, 0.5, 2.0, 0.0]
+    outs = rb.retrieve_many(layers, g_merged, g_base, req, lams)
+    for q in range(len(req)):
+        want = oracle.retrieve(layers, o_merged, np_lists(base), req[q], lams[q],
+                               CODE[d_merged], CODE[dt], CODE[dt], n_threads=8)
+        for l in range(len(stack)):
+            compare(outs[q][l], want[l], "%s request %d layer %d" % (case, q, l))
+
+
+def test_retrieve_many_rejects_overlapping_outputs():
+    stack = aligned_stack()[:3]
+    layers = layers_of(stack)
+    base, deltas = cpu_inputs(stack, 2, "f32")
+    g_merged = rb.merge(layers, [to_gpu(d) for d in deltas], [1, 2])
+    g_base = to_gpu(base)
+    one = rb.alloc_like_layers(layers, torch.float32)
+    with pytest.raises(rb.RandesError):      # two requests into one output stack
+        rb.retrieve_many(layers, g_merged, g_base, [1, 2], [1.0, 1.0], outs=[one, one])
+    with pytest.raises(rb.RandesError):      # an output stack that is the base
+        rb.retrieve_many(layers, g_merged, g_base, [1, 2], [1.0, 1.0], outs=[one, g_base])
+    with pytest.raises(rb.RandesError):
+        rb.retrieve_many(layers, g_merged, g_base, [1, 2], [1.0, float("nan")])

@@ -93,6 +93,15 @@ def test_bad_arguments_are_error_codes_not_crashes(lib):
     assert lib.randes_retrieve(one, 1, ptr, 0, ptr, 0, 1, ctypes.c_float(float("nan")), ptr, 0, None) == EINVAL
     assert lib.randes_retrieve(one, 1, ptr, 0, ptr, 0, 1, ctypes.c_float(float("inf")), ptr, 0, None) == EINVAL
     assert lib.randes_retrieve(one, 1, ptr, 0, None, 0, 1, ctypes.c_float(1.0), ptr, 0, None) == EINVAL
+    lam1 = (ctypes.c_float * 1)(1.0)
+    assert lib.randes_retrieve_many(one, 1, ptr, 0, ptr, 0, 0, seeds, lam1, ptr, 0, None) == EINVAL
+    assert lib.randes_retrieve_many(one, 1, ptr, 0, ptr, 0, 1, None, lam1, ptr, 0, None) == EINVAL
+    assert lib.randes_retrieve_many(one, 1, ptr, 0, ptr, 0, 1, seeds, None, ptr, 0, None) == EINVAL
+    assert lib.randes_retrieve_many(one, 1, ptr, 0, ptr, 0, 1, seeds, lam1, null, 0, None) == EINVAL
+    assert lib.randes_retrieve_many(one, 1, ptr, 0, ptr, 0, 1, seeds, lam1, odd, 0, None) == EINVAL
+    # out == merged == base: overlap is refused before anything is launched
+    assert lib.randes_retrieve_many(one, 1, ptr, 0, ptr, 0, 1, seeds, lam1, ptr, 0, None) == EINVAL
+    assert b"overlap" in lib.randes_strerror(EINVAL)
     # mismatched group shapes
     two = (L * 2)(L(4, 4, 0, 3), L(4, 8, 0, 3))
     out = (ctypes.c_int32 * 2)()
