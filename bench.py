@@ -221,6 +221,34 @@ def widened_rows(lt, per_model_tables, t_deltas, t_merged, t_base, seeds, n_elem
     return {name: {"ms": ms, "GBs": n_elem * bpe / (ms * 1e-3) / 1e9} for name, (bpe, ms) in rows.items()}
 
 
+MANY_Q = 4     # models retrieved per pass in the several-models measurement
+
+
+def many_extras(lt, t_merged, t_base, outs, seeds, n_elem, eb, single_ms):
+    """MANY_Q models retrieved in one pass (the merged stack is read once for all of them), after the
+    timed region.  Reported per request, as algorithmic bytes of MANY_Q single retrievals and as the
+    bytes the pass really moves."""
+    q = len(outs)
+    t_outs = rb.PtrTable([t for per in outs for t in per], lt)
+    req = [seeds[i % len(seeds)] for i in range(q)]
+    lams = [1.0] * q
+
+    def run():
+        rb.retrieve_many(lt, t_merged, t_base, req, lams, outs=t_outs)
+    run()
+    ts = []
+    for _ in range(6):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(); run(); b.record(); b.synchronize()
+        ts.append(a.elapsed_time(b))
+    ms = sorted(ts)[len(ts) // 2]
+    moved = n_elem * eb * (1 + 2 * q)
+    return {"requests_per_pass": q, "ms_per_pass": ms, "ms_per_request": ms / q,
+            "speedup_over_single_requests": single_ms * q / ms,
+            "GBs_algorithmic (3 streams per request)": n_elem * eb * 3 * q / (ms * 1e-3) / 1e9,
+            "GBs_moved (1 + 2 q streams)": moved / (ms * 1e-3) / 1e9}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -248,6 +276,7 @@ def main():
     stack_elems = wl.stack_elements(stack, td)
     placed = {"policy": "plain"}
     place = merged_into = out_into = None
+    more_out_into = []
     if args.placement == "groups" and stack_elems * eb >= (256 << 20):
         # everything but a reserve for temporaries goes into one allocation, cut by measurement
         free_bytes, _ = torch.cuda.mem_get_info()
@@ -257,7 +286,9 @@ def main():
             t_cls = time.perf_counter()
             labels = arena.classify()
             t_cls = time.perf_counter() - t_cls
-            layout = placement.plan_serving_layout(labels, arena.chunk_bytes, stack_elems * eb, K)
+            # three more output stacks, if there is room, for the several-models-per-pass measurement
+            layout = (placement.plan_serving_layout(labels, arena.chunk_bytes, stack_elems * eb, K, MANY_Q - 1)
+                      or placement.plan_serving_layout(labels, arena.chunk_bytes, stack_elems * eb, K))
             placed = {"policy": "plain (no usable address groups found)", "classify_s": t_cls,
                       "runs_gib": [(g, a, b) for g, a, b in placement.runs_of(labels)]}
         except (RuntimeError, ValueError) as e:      # the large allocation itself failed
@@ -269,11 +300,13 @@ def main():
                           "deltas in what is left of every group but the first",
                 "read_group": layout["read_group"], "write_groups": layout["write_groups"],
                 "offsets_gib": {"merged": gib(layout["merged"]), "base": gib(layout["base"]),
-                                "out": gib(layout["out"]), "deltas": [gib(d) for d in layout["deltas"]]}})
+                                "out": gib(layout["out"]), "deltas": [gib(d) for d in layout["deltas"]],
+                                "more_outputs": [gib(d) for d in layout["more_outputs"]]}})
             place = lambda who: arena.flat(layout["base"] if who == "base" else layout["deltas"][who],   # noqa: E731
                                            stack_elems, td)
             merged_into = arena.flat(layout["merged"], stack_elems, td)
             out_into = arena.flat(layout["out"], stack_elems, td)
+            more_out_into = [arena.flat(off, stack_elems, td) for off in layout["more_outputs"]]
         else:
             del arena
             torch.cuda.empty_cache()
@@ -390,6 +423,20 @@ def main():
         per_model = [rb.PtrTable(deltas[i], lt) for i in range(min(K, 2))]
         result["config"]["other_entry_points"] = widened_rows(lt, per_model, t_deltas, t_merged, t_base, seeds,
                                                               n_elem, eb, K)
+        # further output stacks: inside the arena when it was cut, else new allocations if they fit
+        many_outs = [out]
+        try:
+            for i in range(MANY_Q - 1):
+                into = more_out_into[i] if i < len(more_out_into) else None
+                if into is None and torch.cuda.mem_get_info()[0] < stack_elems * eb + (4 << 30):
+                    break
+                many_outs.append(wl.alloc_stack(stack, td, "cuda", into=into)[1])
+        except RuntimeError:
+            pass
+        if len(many_outs) == MANY_Q:
+            result["config"]["retrieve_many"] = many_extras(lt, t_merged, t_base, many_outs, seeds, n_elem, eb,
+                                                            retr_avg)
+        del many_outs
         result["config"]["lora_front_end"] = lora_extras()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(stack, deltas, base, seeds, dtype, n_req, args.cpu_sample_elems)

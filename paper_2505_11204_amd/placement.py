@@ -97,13 +97,14 @@ def _align_up(x, a=256):
     return (x + a - 1) // a * a
 
 
-def plan_serving_layout(labels, chunk_bytes, stack_bytes, n_models):
+def plan_serving_layout(labels, chunk_bytes, stack_bytes, n_models, n_more_outputs=0):
     """Byte offsets of the stacks of one serving set-up inside the classified allocation.
 
-    Returns ``{"merged", "base", "out", "deltas": [...], "read_group", "write_groups"}`` or
+    Returns ``{"merged", "base", "out", "deltas": [...], "more_outputs": [...], "read_group", "write_groups"}`` or
     None when the groups found do not allow the layout: the output stack lies across a
     boundary between two groups, half on either side; merged deltas and base lie in a
-    third group; the models' deltas fill what is left of every group but that third.
+    third group; the models' deltas, then ``n_more_outputs`` further output stacks (for several
+    retrievals in one pass), fill what is left of every group but that third.
     Every stack is contiguous and stays one chunk away from the other group boundaries,
     whose position is only known to one chunk.
     """
@@ -148,9 +149,10 @@ def plan_serving_layout(labels, chunk_bytes, stack_bytes, n_models):
             merged = take(fr, lambda g: g == read_group)
             base = take(fr, lambda g: g == read_group)
             deltas = [take(fr, lambda g: g != read_group) for _ in range(n_models)]
-            if merged is None or base is None or any(d is None for d in deltas):
+            more = [take(fr, lambda g: g != read_group) for _ in range(n_more_outputs)]
+            if merged is None or base is None or any(d is None for d in deltas + more):
                 continue
-            return {"merged": merged, "base": base, "out": out_off, "deltas": deltas,
+            return {"merged": merged, "base": base, "out": out_off, "deltas": deltas, "more_outputs": more,
                     "read_group": read_group, "write_groups": (g1, g2)}
     return None
 

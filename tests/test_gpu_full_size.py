@@ -186,3 +186,24 @@ def test_vit_l14_twenty_tasks_every_element():
 def test_llama_7b_bf16_every_element():
     K = 8
     _every_element_parity(wl.llama_7b(), K, "bf16", [42 + i for i in range(K)], 1.0, [3], 5e-4)
+
+
+def test_llama_7b_four_models_in_one_pass_sampled_rows():
+    # the several-models-per-pass kernel at the 7B launch size (two models merged, four requests)
+    stack = wl.llama_7b()
+    layers = layers_of(stack)
+    K, dtype = 2, "bf16"
+    seeds = [42, 43]
+    base, deltas = wl.make_inputs(stack, K, dtype=dtype, device="cuda", data_seed=1234, delta_std=5e-4)
+    gm = rb.merge(layers, deltas, seeds)
+    req, lams = [43, 42, 42, 43], [1.0, 0.5, 1.0, 0.3]
+    outs = rb.retrieve_many(layers, gm, base, req, lams)
+    torch.cuda.synchronize()
+    rs = _row_sets(stack)
+    sh = _shadow(stack, rs)
+    sh_m, sh_b = gather_rows(gm, rs), gather_rows(base, rs)
+    for q in range(4):
+        want = oracle.retrieve(sh, sh_m, sh_b, req[q], lams[q], CODE[dtype], CODE[dtype], CODE[dtype], n_threads=8)
+        got = gather_rows(outs[q], rs)
+        for l in range(len(stack)):
+            _same_bits(got[l], want[l], "request %d layer %d" % (q, l))

@@ -95,6 +95,17 @@ def test_layout_on_groups_in_several_runs():
     check_layout(labels, lay, 8)
 
 
+def test_layout_with_more_output_stacks():
+    labels = [1] * 96 + [0] * 96 + [2] * 82
+    lay = pl.plan_serving_layout(labels, GIB, STACK, 8, n_more_outputs=3)
+    check_layout(labels, lay, 8)
+    spans = sorted([lay["merged"], lay["base"], lay["out"]] + lay["deltas"] + lay["more_outputs"])
+    assert len(lay["more_outputs"]) == 3 and all(b - a >= STACK for a, b in zip(spans, spans[1:]))
+    for off in lay["more_outputs"]:
+        assert lay["read_group"] not in {labels[c] for c in range(off // GIB, (off + STACK - 1) // GIB + 1)}
+    assert pl.plan_serving_layout(labels, GIB, STACK, 8, n_more_outputs=9) is None     # no room outside the read group
+
+
 def test_layout_needs_room():
     labels = [0] * 20 + [1] * 20 + [2] * 20          # 60 GiB cannot hold eleven 12.55 GiB stacks
     assert pl.plan_serving_layout(labels, GIB, STACK, 8) is None
