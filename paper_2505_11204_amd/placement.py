@@ -202,3 +202,30 @@ class Arena:
         if end > self.buf.numel():
             raise ValueError("range past the end of the arena")
         return self.buf[byte_offset:end].view(dtype)
+
+
+def main(argv=None):
+    """Print what the classification finds on this machine, and the map of copy rates behind it
+    (read chunk x write chunk at regular positions of one large allocation)."""
+    import argparse
+    ap = argparse.ArgumentParser(description=main.__doc__)
+    ap.add_argument("--reserve-gib", type=int, default=12, help="device memory left outside the allocation")
+    ap.add_argument("--step-gib", type=int, default=8, help="distance between the positions of the map")
+    args = ap.parse_args(argv)
+    rb.lib()
+    free_bytes, total_bytes = torch.cuda.mem_get_info()
+    arena = Arena(free_bytes - args.reserve_gib * GIB)
+    labels = arena.classify()
+    print("device memory %.1f GiB, allocation of %d chunks of 1 GiB" % (total_bytes / GIB, arena.n_chunks))
+    print("group of every chunk: " + "".join(str(g) for g in labels))
+    print("runs (group, first GiB, end GiB): " + ", ".join("(%d, %d, %d)" % r for r in runs_of(labels)))
+    pos = list(range(0, arena.n_chunks - 1, args.step_gib))
+    print("copy rate in units of 100 GB/s; rows: position of the chunk read (GiB), columns: of the chunk written")
+    print("      " + " ".join("%3d" % p for p in pos))
+    for r in pos:
+        print("%4d: " % r + " ".join(" . " if r == w else "%3d" % round(arena.copy_rate(r, w) * 1e-8) for w in pos))
+    return 0
+
+
+if __name__ == "__main__":
+    raise SystemExit(main())
