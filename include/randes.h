@@ -25,7 +25,11 @@
  *  - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
  *    the default stream).  Calls do not synchronise; results are valid once
  *    the caller has synchronised the stream.  Buffers must stay alive until
- *    then.
+ *    then.  The first call with a given argument set builds its tables on the
+ *    host and uploads them synchronously (hipMalloc + hipMemcpy); a repeated
+ *    call only launches kernels and may therefore be recorded into a HIP
+ *    graph.  At most 64 argument sets stay cached; the least recently used
+ *    one is dropped (hipFree, which waits for the device).
  *  - Layer pointers must be aligned to their element size (else RANDES_EINVAL).
  *    16-byte aligned layers whose cols is a multiple of 4 (f32) / 8 (bf16)
  *    take the vectorised kernels; anything else takes a slower element-wise

@@ -17,15 +17,8 @@ typedef RANDES_GLOBAL char *gptr;          // writable global bytes
 constexpr int WG = 256;          // threads per workgroup
 constexpr int WAVES = WG / 64;
 constexpr int KREG_MAX = 8;      // merge: up to this many tasks keep their masks in registers
-#ifndef RANDES_MERGE_R
-#define RANDES_MERGE_R 4
-#endif
-#ifndef RANDES_STORE_AT_END
-#define RANDES_STORE_AT_END 1
-#endif
-constexpr bool STORE_AT_END = RANDES_STORE_AT_END != 0;   // hold a burst's results until all of them exist
-constexpr int MERGE_R = RANDES_MERGE_R;          // merge: rows a wave loads before it stores (one burst)
-constexpr int MERGE_WEIGHTS_R = MERGE_R / 2 > 0 ? MERGE_R / 2 : 1;   // merge from weights: two streams per task
+constexpr int MERGE_R = 4;       // merge: rows a wave loads before it stores (one burst)
+constexpr int MERGE_WEIGHTS_R = 2;   // merge from weights: two streams per task, half the rows
 
 __device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }
 __device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }

@@ -328,14 +328,11 @@ __global__ void __launch_bounds__(WG) merge_kernel(const StreamArgs A)
                     else accumulate_w<DTI, VEC>(raw[j][i], W[i], acc);
                 }
                 pack_out<DTO, VEC>(acc, res[j]);
-                if (!STORE_AT_END) store_words<DTO, VEC>(dst + (off_out + j * step_out), res[j]);
             }
-        if (STORE_AT_END) {
-            load_store_fence();
+        load_store_fence();
 #pragma unroll
-            for (int j = 0; j < R; ++j)
-                if (r + t.WY * j < t.row_end) store_words<DTO, VEC>(dst + (off_out + j * step_out), res[j]);
-        }
+        for (int j = 0; j < R; ++j)
+            if (r + t.WY * j < t.row_end) store_words<DTO, VEC>(dst + (off_out + j * step_out), res[j]);
     } else {
         const uint32_t nblk = stage_sign_bits(sbits, t, A.keys, K, 0u, 0u);
         for (uint32_t i = threadIdx.x; i < NS * K; i += WG)
@@ -447,14 +444,11 @@ __device__ __forceinline__ void two_input_bursts(const StreamArgs &A, const Tile
                 o[j] = FMA ? __builtin_fmaf(lambda, xs, y[j]) : (y[j] + xs);
             }
             pack_out<DTO, VEC>(o, res[u]);
-            if (!STORE_AT_END) store_words<DTO, VEC>(po + (e + u * estep) * EBO, res[u]);
         }
-    if (STORE_AT_END) {
-        load_store_fence();
+    load_store_fence();
 #pragma unroll
-        for (int u = 0; u < R; ++u)
-            if (r + t.WY * u < t.row_end) store_words<DTO, VEC>(po + (e + u * estep) * EBO, res[u]);
-    }
+    for (int u = 0; u < R; ++u)
+        if (r + t.WY * u < t.row_end) store_words<DTO, VEC>(po + (e + u * estep) * EBO, res[u]);
 }
 
 template <int DTM, int DTB, int DTO, int VEC>

@@ -521,3 +521,84 @@ def test_retrieve_many_rejects_overlapping_outputs():
         rb.retrieve_many(layers, g_merged, g_base, [1, 2], [1.0, 1.0], outs=[one, g_base])
     with pytest.raises(rb.RandesError):
         rb.retrieve_many(layers, g_merged, g_base, [1, 2], [1.0, float("nan")])
+
+
+def test_plan_cache_eviction_and_reuse():
+    # more distinct calls than the cache holds: old tables are dropped, results stay right, and a
+    # call whose tables were dropped builds them again
+    stack = [Layer(40, 264, 0, SRSF), Layer(40, 264, 0, SRSF), Layer(9, 77, -1, FLIP)]
+    layers = layers_of(stack)
+    base, deltas = cpu_inputs(stack, 2, "f32")
+    seeds = [5, 6]
+    g_d = [to_gpu(d) for d in deltas]
+    g_merged = rb.merge(layers, g_d, seeds)
+    o_merged = oracle.merge(layers, [np_lists(d) for d in deltas], seeds, 0, 0)
+    g_base = to_gpu(base)
+    out = rb.alloc_like_layers(layers, torch.float32)
+    for rnd in range(2):
+        for s in range(80):           # 80 different seeds = 80 different source tables
+            rb.retrieve(layers, g_merged, g_base, 1000 + s, 1.0, out=out)
+            if s in (0, 41, 79):
+                want = oracle.retrieve(layers, o_merged, np_lists(base), 1000 + s, 1.0, 0, 0, 0)
+                for l in range(len(stack)):
+                    compare(out[l], want[l], "round %d seed %d layer %d" % (rnd, s, l))
+    again = rb.merge(layers, g_d, seeds)      # its tables were dropped long ago
+    for l in range(len(stack)):
+        compare(again[l], o_merged[l], "merged again %d" % l)
+
+
+def test_cached_calls_can_be_captured_in_a_graph():
+    # once a call's tables are cached it only launches kernels, so it can be recorded into a HIP
+    # graph; every replay must give what the eager call gives on the data of that moment
+    stack = aligned_stack()
+    layers = layers_of(stack)
+    K, dt = 3, "bf16"
+    seeds = [11, 12, 13]
+    base, deltas = cpu_inputs(stack, K, dt)
+    g_d = [to_gpu(d) for d in deltas]
+    g_base = to_gpu(base)
+    lt = rb.LayerTable(layers)
+    t_d = rb.PtrTable([t for per in g_d for t in per], lt)
+    merged = rb.alloc_like_layers(layers, TD[dt])
+    out = rb.alloc_like_layers(layers, TD[dt])
+    t_m, t_b, t_o = rb.PtrTable(merged, lt), rb.PtrTable(g_base, lt), rb.PtrTable(out, lt)
+    stats = torch.zeros(3, dtype=torch.float64, device="cuda")
+    t_d0, t_d1 = rb.PtrTable(g_d[0], lt), rb.PtrTable(g_d[1], lt)
+
+    def run():
+        rb.merge(lt, t_d, seeds, merged=t_m)
+        rb.retrieve(lt, t_m, t_b, seeds[1], 0.5, out=t_o)
+        rb.delta_stats(lt, t_d0, seeds[0], t_d1, seeds[1], out=stats)
+    run()                                   # builds and caches the tables
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        run()
+        graph.capture_end()
+    torch.cuda.synchronize()
+    for rnd in range(3):
+        # new data in the same buffers, eager result first
+        for per in g_d:
+            for t in per:
+                t.mul_(1.5 + rnd)
+        run()
+        torch.cuda.synchronize()
+        want_m = [t.clone() for t in merged]
+        want_o = [t.clone() for t in out]
+        want_s = stats.clone()
+        for t in merged + out:
+            t.zero_()
+        stats.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for l in range(len(stack)):
+            assert torch.equal(merged[l].view(torch.int16), want_m[l].view(torch.int16)), (rnd, l)
+            assert torch.equal(out[l].view(torch.int16), want_o[l].view(torch.int16)), (rnd, l)
+        assert torch.equal(stats, want_s)
+    # and the eager result is the oracle's
+    o_m = oracle.merge(layers, [[to_np(t) for t in per] for per in g_d], seeds, CODE[dt], CODE[dt], n_threads=8)
+    for l in range(len(stack)):
+        compare(merged[l], o_m[l], "graph replay, merged %d" % l)
