@@ -219,6 +219,21 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
 
     constexpr int NF = RES > 0 ? RES : 1;
     u32x4 frag[NF][4];   // bf16 factors: right-operand fragments per resident slice (RES = 0: of the current slice)
+    // Resident variants with registers to spare fetch a row block's slices of B one block ahead
+    // (the first block's while the slabs are staged), so that no row block waits for global memory.
+    constexpr bool AHEAD = DTAB == DT_BF16 && (RES == 1 || RES == 4);
+    constexpr int NB_AHEAD = AHEAD ? RES : 1;
+    u32x4 bnext[NB_AHEAD];
+    auto fetch_b = [&](int rt, u32x4 *dst) {
+        const int32_t r0 = ((int32_t)ty * LORA_ROW_TILES + rt) * LORA_TILE_M;
+        const int32_t row = r0 + (int32_t)l32;
+#pragma unroll
+        for (int s = 0; s < NF; ++s)
+            if (s < n_slices)
+                dst[s] = lora_b_slice(segs[it.seg_begin + (uint32_t)(s / slices_per_seg)], row, row < rows,
+                                      (s % slices_per_seg) * KCH, half, rank);
+    };
+    if constexpr (AHEAD) fetch_b(0, bnext);
     if constexpr (RES > 0) {
 #pragma unroll
         for (int s = 0; s < RES; ++s) {
@@ -248,11 +263,13 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
     if constexpr (RES > 0) {
         if constexpr (DTAB == DT_BF16) {
             u32x4 bsl[RES];   // all loads of the row block go out before the first multiply
+            if constexpr (AHEAD) {
 #pragma unroll
-            for (int s = 0; s < RES; ++s)
-                if (s < n_slices)
-                    bsl[s] = lora_b_slice(segs[it.seg_begin + (uint32_t)(s / slices_per_seg)], my_row, row_ok,
-                                          (s % slices_per_seg) * KCH, half, rank);
+                for (int s = 0; s < RES; ++s) bsl[s] = bnext[s];
+                if (rt + 1 < LORA_ROW_TILES && row0 + LORA_TILE_M < rows) fetch_b(rt + 1, bnext);
+            } else {
+                fetch_b(rt, bsl);
+            }
 #pragma unroll
             for (int s = 0; s < RES; ++s)
                 if (s < n_slices) {
