@@ -673,11 +673,12 @@ int run_lora(std::vector<LoraItem> &items, const std::vector<LoraSeg> &segs, int
 {
     uint64_t tiles = 0;
     uint32_t max_seg = 1;
+    for (const LoraItem &it : items) max_seg = std::max(max_seg, it.n_seg);
+    const int64_t wg_rows = (int64_t)LORA_TILE_M * lora_row_tiles((int32_t)max_seg, rank);
     for (LoraItem &it : items) {
-        max_seg = std::max(max_seg, it.n_seg);
         it.tiles_x = (uint32_t)(((int64_t)it.cols + LORA_TILE_N - 1) / LORA_TILE_N);
         it.tile_begin = (uint32_t)tiles;
-        tiles += (uint64_t)it.tiles_x * (uint64_t)(((int64_t)it.rows + LORA_TILE_M * LORA_ROW_TILES - 1) / (LORA_TILE_M * LORA_ROW_TILES));
+        tiles += (uint64_t)it.tiles_x * (uint64_t)(((int64_t)it.rows + wg_rows - 1) / wg_rows);
         if (tiles >= ((uint64_t)1 << 31)) return fail(RANDES_ENOTSUP, "too many tiles for one launch");
     }
     int dev, rc;

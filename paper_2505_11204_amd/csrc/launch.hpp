@@ -42,6 +42,7 @@ struct LoraSeg {
 // segments of any matrix (chooses the kernel variant).
 hipError_t launch_lora(const LoraItem *items_dev, int32_t n_items, const LoraSeg *segs_dev, const uint32_t *coarse_dev,
                        uint32_t n_tiles, int32_t max_seg, int32_t rank, float scale, int dt_ab, int dt_out, hipStream_t s);
+// (the tile count must have been computed with lora_row_tiles(max_seg, rank) row blocks per workgroup)
 
 // Columns per lane of the vector kernels for a call whose widest-count stream
 // holds bf16 (8) or only f32 (4).
@@ -77,6 +78,15 @@ constexpr uint64_t PROBE_CHUNK_BYTES = 4u * 256u * 16u;
 hipError_t launch_probe(const void *const *inputs, int n_inputs, void *output, uint64_t bytes, int write, hipStream_t s);
 
 // Workgroup tile of the LoRA kernel.
-constexpr int LORA_TILE_M = 32, LORA_TILE_N = 512, LORA_ROW_TILES = 4;
+constexpr int LORA_TILE_M = 32, LORA_TILE_N = 512;
+constexpr int LORA_DEPTH_SLICE = 16;    // depth (segments x rank) handled per staged slab
+// Blocks of LORA_TILE_M rows one workgroup handles, one after the other, with the same staged
+// operand fragments: 4 when the product is one depth slice deep (measured best for plain
+// materialisation), 8 when it is deeper and staging costs more (superposed adapters, rank > 16).
+inline int lora_row_tiles(int32_t max_seg, int32_t rank)
+{
+    const int64_t slices = (int64_t)max_seg * ((rank + LORA_DEPTH_SLICE - 1) / LORA_DEPTH_SLICE);
+    return slices <= 1 ? 4 : 8;
+}
 
 }  // namespace randes

@@ -7,7 +7,7 @@
 // with the sign diagonal D of its model, is the superposition of K adapters written once:
 // sum_i (B_i A_i) D_i = [B_1 .. B_K] [A_1 D_1; ..; A_K D_K], a rank K*r contraction.
 //
-// A workgroup (4 waves) owns 512 columns and LORA_ROW_TILES consecutive blocks of 32 rows; per block
+// A workgroup (4 waves) owns 512 columns and 4 or 8 consecutive blocks of 32 rows; per block
 // each wave owns 32 x 128 = four 32x32 MFMA accumulators.  Per 16-deep slice of the depth (segments
 // x rank) the workgroup stages A's 16 x 512 slab, sign-flipped, into LDS with 16-byte accesses
 // (row-major, as in memory); a lane then gathers the 8 depth values of its column with 2-byte LDS
@@ -46,7 +46,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-constexpr int KCH = 16;                 // rank slice per staging step
+constexpr int KCH = LORA_DEPTH_SLICE;   // rank slice per staging step
 constexpr int AS_STRIDE = LORA_TILE_N + 8;   // elements per staged depth row (keeps rows 16-byte aligned)
 constexpr int ST_ROW_BYTES = 272;       // staged output row: 128 bf16 or 64 binary32 columns, plus 16 bytes
 constexpr int ST_STRIDE = ST_ROW_BYTES / 2;     // in bf16 elements
@@ -189,7 +189,7 @@ __device__ __forceinline__ void lora_mma_f32(const char *smem, const LoraSeg &S,
 // staged again for every row block.
 template <int DTAB, int DTO, int RES>
 __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t n_items, const LoraSeg *segs,
-                                                  const uint32_t *coarse, int32_t rank, float scale)
+                                                  const uint32_t *coarse, int32_t rank, float scale, int32_t row_tiles)
 {
     static_assert(RES >= 0 && RES <= LORA_RESIDENT_MAX && (DTAB == DT_BF16 || RES <= 1), "unsupported residency");
     constexpr int AT_BYTES = KCH * AS_STRIDE * (DTAB == DT_BF16 ? 2 : 4);
@@ -225,7 +225,7 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
     constexpr int NB_AHEAD = AHEAD ? RES : 1;
     u32x4 bnext[NB_AHEAD];
     auto fetch_b = [&](int rt, u32x4 *dst) {
-        const int32_t r0 = ((int32_t)ty * LORA_ROW_TILES + rt) * LORA_TILE_M;
+        const int32_t r0 = ((int32_t)ty * row_tiles + rt) * LORA_TILE_M;
         const int32_t row = r0 + (int32_t)l32;
 #pragma unroll
         for (int s = 0; s < NF; ++s)
@@ -248,8 +248,8 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
         }
     }
 
-  for (int rt = 0; rt < LORA_ROW_TILES; ++rt) {
-    const int32_t row0 = ((int32_t)ty * LORA_ROW_TILES + rt) * LORA_TILE_M;
+  for (int rt = 0; rt < row_tiles; ++rt) {
+    const int32_t row0 = ((int32_t)ty * row_tiles + rt) * LORA_TILE_M;
     if (row0 >= rows) break;
     const int32_t my_row = row0 + (int32_t)l32;              // left-operand row of this lane
     const bool row_ok = my_row < rows;
@@ -266,7 +266,7 @@ __global__ void __launch_bounds__(WG) lora_kernel(const LoraItem *items, int32_t
             if constexpr (AHEAD) {
 #pragma unroll
                 for (int s = 0; s < RES; ++s) bsl[s] = bnext[s];
-                if (rt + 1 < LORA_ROW_TILES && row0 + LORA_TILE_M < rows) fetch_b(rt + 1, bnext);
+                if (rt + 1 < row_tiles && row0 + LORA_TILE_M < rows) fetch_b(rt + 1, bnext);
             } else {
                 fetch_b(rt, bsl);
             }
@@ -388,8 +388,9 @@ hipError_t launch_lora(const LoraItem *items_dev, int32_t n_items, const LoraSeg
     if (n_tiles == 0) return hipSuccess;
     const dim3 grid(n_tiles), block(WG);
     const int64_t slices = (int64_t)max_seg * ((rank + KCH - 1) / KCH);   // depth slices of the deepest matrix
+    const int32_t row_tiles = lora_row_tiles(max_seg, rank);
 #define RANDES_LORA(DA, DO, RES) hipLaunchKernelGGL((lora_kernel<DA, DO, RES>), grid, block, 0, s, items_dev, n_items, \
-                                                    segs_dev, coarse_dev, rank, scale)
+                                                    segs_dev, coarse_dev, rank, scale, row_tiles)
     if (dt_ab == DT_BF16) {
         // fragments of 1, up to 4 or up to 8 slices in registers (92 / ~150 / 245 registers per lane)
         const int res = slices <= 1 ? 1 : (slices <= 4 ? 4 : (slices <= LORA_RESIDENT_MAX ? LORA_RESIDENT_MAX : 0));
