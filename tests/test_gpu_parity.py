@@ -602,3 +602,54 @@ def test_cached_calls_can_be_captured_in_a_graph():
     o_m = oracle.merge(layers, [[to_np(t) for t in per] for per in g_d], seeds, CODE[dt], CODE[dt], n_threads=8)
     for l in range(len(stack)):
         compare(merged[l], o_m[l], "graph replay, merged %d" % l)
+
+
+@pytest.mark.parametrize("trial", range(24))
+def test_random_stacks_through_every_streaming_entry_point(trial):
+    # randomly drawn stacks (shapes on and off the vector path, random groups and flags), model
+    # counts, dtypes and scales; merge, retrieve, several retrievals per pass, hot add / remove and
+    # merge-from-weights against the oracle
+    rnd = np.random.RandomState(7000 + trial)
+    shapes = [(rnd.randint(1, 70), int(rnd.choice([1, 7, 8, 64, 130, 136, 520, 1032, 2056]))) for _ in range(3)]
+    stack = []
+    for _ in range(rnd.randint(1, 9)):
+        g = int(rnd.randint(-1, 3))
+        rows, cols = shapes[g] if g >= 0 else (rnd.randint(1, 40), int(rnd.choice([3, 8, 24, 100, 264])))
+        flags = int(rnd.choice([0, FLIP, SHUFFLE, SRSF, SRSF, SRSF]))
+        stack.append(Layer(int(rows), int(cols), g, flags))
+    if rnd.rand() < 0.25:          # one group shifted instead of shuffled
+        stack = [Layer(l.rows, l.cols, l.group, (l.flags & FLIP) | SHIFT) if l.group == 0 else l for l in stack]
+    layers = layers_of(stack)
+    K = int(rnd.randint(1, 11))
+    d_in = str(rnd.choice(["f32", "bf16"]))
+    d_merged = str(rnd.choice(["f32", "bf16"]))
+    d_out = str(rnd.choice(["f32", "bf16"]))
+    seeds = [int(s) for s in rnd.randint(0, 2 ** 31, size=K)]
+    seeds[0] = (seeds[0] << 33) | 5          # both key halves in use
+    lam = float(rnd.choice([1.0, 0.3, -0.75, 2.0]))
+    gm, om = run_both(stack, K, seeds, d_in, d_merged, d_in, d_out, lam, sorted({0, K - 1}), data_seed=trial)
+    base, deltas = cpu_inputs(stack, K, d_in, trial)
+    g_base = to_gpu(base)
+    # several retrievals in one pass
+    n_req = int(rnd.randint(1, 6))
+    req = [seeds[int(i)] for i in rnd.randint(0, K, size=n_req)]
+    lams = [float(x) for x in rnd.choice([1.0, 0.5, 0.0, -1.25], size=n_req)]
+    outs = rb.retrieve_many(layers, gm, g_base, req, lams, out_dtype=TD[d_out])
+    for q in range(n_req):
+        want = oracle.retrieve(layers, om, np_lists(base), req[q], lams[q], CODE[d_merged], CODE[d_in], CODE[d_out])
+        for l in range(len(stack)):
+            compare(outs[q][l], want[l], "trial %d request %d layer %d" % (trial, q, l))
+    # hot add of a further model, then removal of the first
+    _, extra = cpu_inputs(stack, 1, d_in, trial + 500)
+    rb.update(layers, gm, to_gpu(extra[0]), 31337)
+    oracle.update(layers, om, np_lists(extra[0]), 31337, False, CODE[d_merged], CODE[d_in])
+    rb.update(layers, gm, to_gpu(deltas[0]), seeds[0], remove=True)
+    oracle.update(layers, om, np_lists(deltas[0]), seeds[0], True, CODE[d_merged], CODE[d_in])
+    for l in range(len(stack)):
+        compare(gm[l], om[l], "trial %d after hot swap, layer %d" % (trial, l))
+    # merge straight from weights (here: base + delta rounded to the storage dtype)
+    weights = [[(b.float() + d.float()).to(TD[d_in]) for b, d in zip(base, per)] for per in deltas]
+    gw = rb.merge_weights(layers, [to_gpu(w) for w in weights], g_base, seeds, merged_dtype=TD[d_merged])
+    ow = oracle.merge_weights(layers, [np_lists(w) for w in weights], np_lists(base), seeds, CODE[d_in], CODE[d_merged])
+    for l in range(len(stack)):
+        compare(gw[l], ow[l], "trial %d merge from weights, layer %d" % (trial, l))
