@@ -64,6 +64,8 @@ def parse():
                     help="groups: find the memory's address groups by timing copies and place read and "
                          "write streams in different ones (stacks of 8 GiB and more); plain: one "
                          "allocation per stack, wherever the allocator puts it")
+    ap.add_argument("--no-fold", action="store_true",
+                    help="hand every layer to the kernels row by row (see randes_set_fold)")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the plain-streaming probe")
     ap.add_argument("--no-extras", action="store_true", help="skip the LoRA front-end measurement")
     return ap.parse_args()
@@ -271,6 +273,7 @@ def main():
     seeds = [42 + i for i in range(K)]
     scales = wl.task_scales(K, 1234) if scaled else None
     rb.set_tile_rows(args.merge_rows, args.retrieve_rows)
+    rb.set_fold(not args.no_fold)
 
     td = wl.torch_dtype(dtype)
     stack_elems = wl.stack_elements(stack, td)

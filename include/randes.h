@@ -239,6 +239,12 @@ int randes_set_tile_rows(int32_t merge_rows, int32_t retrieve_rows);
  * Results never depend on it. */
 int randes_set_tile_cols(int32_t max_waves_along_columns);
 
+/* Third launch-shape knob: a layer whose row length leaves lanes of the column tiles idle (768
+ * bf16 columns: a quarter of them) is handed to the kernels with 2..8 consecutive rows shown as
+ * one longer row (rows are contiguous in memory; the sign pattern of Sec. 4.4 then simply repeats
+ * along the longer row).  enable = 0 switches this off (default on).  Results never depend on it. */
+int randes_set_fold(int32_t enable);
+
 /* Measurement aid, not part of the method: a plain streaming kernel with the same
  * launch shape as merge / retrieve and nothing else in it.  Reads n_inputs (1..8)
  * device streams of `bytes` bytes each (16-byte aligned, bytes a multiple of 16384)

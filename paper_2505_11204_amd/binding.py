@@ -25,7 +25,7 @@ LIB_PATH = os.path.join(_HERE, "librandes.so")
 EXPORTS = ["randes_layer_perm", "randes_source_table", "randes_sign_mask", "randes_merge", "randes_merge_weights",
            "randes_retrieve", "randes_retrieve_many", "randes_update", "randes_delta_stats", "randes_lora_materialize",
            "randes_lora_materialize_batched", "randes_lora_merge", "randes_strerror", "randes_shutdown",
-           "randes_set_tile_rows", "randes_set_tile_cols",
+           "randes_set_tile_rows", "randes_set_tile_cols", "randes_set_fold",
            "randes_probe_stream"]
 
 
@@ -74,6 +74,7 @@ def lib():
     L.randes_shutdown.argtypes = []
     L.randes_set_tile_rows.argtypes = [i32, i32]
     L.randes_set_tile_cols.argtypes = [i32]
+    L.randes_set_fold.argtypes = [i32]
     L.randes_probe_stream.argtypes = [vp, i32, vp, i64, i32, vp]
     for name in EXPORTS:
         if name != "randes_strerror":
@@ -396,6 +397,12 @@ def set_tile_rows(merge_rows=0, retrieve_rows=0):
 def set_tile_cols(max_waves_along_columns=0):
     """Second launch-shape knob (4, 2, 1; 0 = default).  Results do not depend on it."""
     _check(lib().randes_set_tile_cols(int(max_waves_along_columns)))
+
+
+def set_fold(enable=True):
+    """Third launch-shape knob: fold rows of layers that leave lanes idle (default on).
+    Results do not depend on it."""
+    _check(lib().randes_set_fold(1 if enable else 0))
 
 
 def probe_stream(inputs, output, write=True, stream=None):

@@ -40,6 +40,10 @@ bool elem_aligned(const void *p, int dtype) { return ((uintptr_t)p & (elem_bytes
 
 int g_merge_rows = 0, g_retrieve_rows = 0;   // rows per wave per tile; 0 = the kernels' burst size
 int g_max_wx_shift = 2;   // widest tile: 4 waves side by side along the columns
+int g_fold = 1;           // 1: rows of layers that leave lanes idle are folded (see fold_factor)
+
+// The launch-shape knobs as one word of a plan's cache key.
+int32_t knob_word(int rows) { return rows * 16 + g_max_wx_shift * 2 + g_fold; }
 
 // A wave handles one burst of at most `burst` rows; the knob can only shrink it.
 int clamp_rows(int knob, int burst) { return (knob <= 0 || knob > burst) ? burst : knob; }
@@ -118,8 +122,37 @@ int upload(HostPlan &hp, int n_tasks, CachedPlan *cp)
     return RANDES_OK;
 }
 
-// Add one slot layer to the vector or element-wise sub-plan.
-int place(HostPlan *hp, LayerDev d, const void *const *srcs, int n_srcs, bool vector_ok, int vec, int rows_per_wave)
+// Bytes per element of the streams a descriptor points to (for pointer arithmetic on pieces of a layer).
+struct StreamBytes { size_t dst, a, b, src; };
+
+int place_piece(HostPlan *hp, LayerDev d, const void *const *srcs, int n_srcs, bool vector_ok, int vec, int rows_per_wave);
+
+// Add one slot layer to the vector or element-wise sub-plan.  A layer on the vector path whose row
+// length leaves lanes idle goes in folded: f rows shown as one, plus the rows % f rows left over.
+int place(HostPlan *hp, LayerDev d, const void *const *srcs, int n_srcs, bool vector_ok, int vec, int rows_per_wave,
+          const StreamBytes &eb)
+{
+    const int f = (vector_ok && g_fold) ? fold_factor(d.rows, d.cols, vec, g_max_wx_shift) : 1;
+    if (f <= 1) return place_piece(hp, d, srcs, n_srcs, vector_ok, vec, rows_per_wave);
+    const int64_t rows = d.rows, cols = d.cols;
+    LayerDev fd = d;
+    fd.rows = (int32_t)(rows / f);
+    fd.cols = (int32_t)(cols * f);
+    fd.sign_blocks = (uint32_t)(cols / 128);
+    int rc = place_piece(hp, fd, srcs, n_srcs, true, vec, rows_per_wave);
+    if (rc || rows % f == 0) return rc;
+    const size_t skip = (size_t)(rows / f) * (size_t)f * (size_t)cols;   // elements before the left-over rows
+    LayerDev rd = d;
+    rd.rows = (int32_t)(rows % f);
+    if (rd.dst) rd.dst = (char *)rd.dst + skip * eb.dst;
+    if (rd.a) rd.a = (const char *)rd.a + skip * eb.a;
+    if (rd.b) rd.b = (const char *)rd.b + skip * eb.b;
+    std::vector<const void *> moved((size_t)n_srcs);
+    for (int i = 0; i < n_srcs; ++i) moved[(size_t)i] = (const char *)srcs[i] + skip * eb.src;
+    return place_piece(hp, rd, moved.data(), n_srcs, true, vec, rows_per_wave);
+}
+
+int place_piece(HostPlan *hp, LayerDev d, const void *const *srcs, int n_srcs, bool vector_ok, int vec, int rows_per_wave)
 {
     SubPlan &sp = vector_ok ? hp->vec : hp->scl;
     const uint64_t tiles = plan_layer_geometry(&d, vector_ok ? vec : 1, rows_per_wave, g_max_wx_shift);
@@ -223,7 +256,7 @@ int merge_impl(const randes_layer *layers, int32_t n_layers,
     int dev;
     if ((rc = current_device(&dev))) return rc;
     std::lock_guard<std::mutex> lock(g_mu);
-    const int32_t tile_rows = g_merge_rows * 4 + g_max_wx_shift;   // both knobs, for the cache key
+    const int32_t tile_rows = knob_word(g_merge_rows);   // the knobs, for the cache key
     std::string key;
     const int32_t head[6] = { base ? PLAN_MERGE_WEIGHTS : PLAN_MERGE, n_layers, n_tasks, (int32_t)delta_dtype, (int32_t)merged_dtype, tile_rows };
     append(&key, head, sizeof(head));
@@ -276,7 +309,8 @@ int merge_impl(const randes_layer *layers, int32_t n_layers,
                 }
             }
             const int burst = base ? merge_weights_burst_rows() : merge_burst_rows();
-            if ((rc = place(&hp, d, ptrs.data(), n_streams, vector_ok, vec, clamp_rows(g_merge_rows, burst)))) return rc;
+            const StreamBytes eb{ elem_bytes(merged_dtype), 0, 0, elem_bytes(delta_dtype) };
+            if ((rc = place(&hp, d, ptrs.data(), n_streams, vector_ok, vec, clamp_rows(g_merge_rows, burst), eb))) return rc;
         }
         CachedPlan fresh;
         fresh.key = key;
@@ -335,7 +369,7 @@ int randes_retrieve(const randes_layer *layers, int32_t n_layers,
     int dev;
     if ((rc = current_device(&dev))) return rc;
     std::lock_guard<std::mutex> lock(g_mu);
-    const int32_t tile_rows = g_retrieve_rows * 4 + g_max_wx_shift;   // both knobs, for the cache key
+    const int32_t tile_rows = knob_word(g_retrieve_rows);   // the knobs, for the cache key
     std::string key;
     const int32_t head[6] = { PLAN_RETRIEVE, n_layers, (int32_t)merged_dtype, (int32_t)base_dtype, (int32_t)out_dtype, tile_rows };
     append(&key, head, sizeof(head));
@@ -377,7 +411,8 @@ int randes_retrieve(const randes_layer *layers, int32_t n_layers,
             d.flip = (layers[l].flags & RANDES_FLIP) ? 1u : 0u;
             const bool vector_ok = (layers[l].cols % vec) == 0 && aligned16(d.dst) && aligned16(d.a) && aligned16(d.b);
             const int burst = two_input_burst_rows(merged_dtype, base_dtype, vector_ok ? vec : 1);
-            if ((rc = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(g_retrieve_rows, burst)))) return rc;
+            const StreamBytes eb{ elem_bytes(out_dtype), elem_bytes(merged_dtype), elem_bytes(base_dtype), 0 };
+            if ((rc = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(g_retrieve_rows, burst), eb))) return rc;
         }
         CachedPlan fresh;
         fresh.key = key;
@@ -410,7 +445,7 @@ int retrieve_many_pass(const randes_layer *layers, int32_t n_layers, const void 
     if ((rc = current_device(&dev))) return rc;
     std::lock_guard<std::mutex> lock(g_mu);
     std::string key, why;
-    const int32_t head[5] = { PLAN_RETRIEVE_MANY, n_layers, dtype, q, g_max_wx_shift };
+    const int32_t head[5] = { PLAN_RETRIEVE_MANY, n_layers, dtype, q, knob_word(0) };
     append(&key, head, sizeof(head));
     append(&key, layers, sizeof(randes_layer) * (size_t)n_layers);
     append(&key, merged, sizeof(void *) * (size_t)n_layers);
@@ -441,7 +476,8 @@ int retrieve_many_pass(const randes_layer *layers, int32_t n_layers, const void 
                 ptrs[(size_t)i] = base[t];
                 ptrs[(size_t)(q + i)] = outs[(size_t)i * n_layers + t];
             }
-            if ((rc = place(&hp, d, ptrs.data(), 2 * q, true, vec, retrieve_many_rows(q)))) return rc;
+            const StreamBytes eb{ 0, elem_bytes(dtype), 0, elem_bytes(dtype) };
+            if ((rc = place(&hp, d, ptrs.data(), 2 * q, true, vec, retrieve_many_rows(q), eb))) return rc;
         }
         CachedPlan fresh;
         fresh.key = key;
@@ -540,7 +576,7 @@ int randes_update(const randes_layer *layers, int32_t n_layers,
     int dev;
     if ((rc = current_device(&dev))) return rc;
     std::lock_guard<std::mutex> lock(g_mu);
-    const int32_t tile_rows = g_retrieve_rows * 4 + g_max_wx_shift;   // both knobs, for the cache key
+    const int32_t tile_rows = knob_word(g_retrieve_rows);   // the knobs, for the cache key
     std::string key;
     const int32_t head[5] = { PLAN_UPDATE, n_layers, (int32_t)merged_dtype, (int32_t)delta_dtype, tile_rows };
     append(&key, head, sizeof(head));
@@ -573,7 +609,8 @@ int randes_update(const randes_layer *layers, int32_t n_layers,
             d.flip = (layers[l].flags & RANDES_FLIP) ? 1u : 0u;
             const bool vector_ok = (layers[l].cols % vec) == 0 && aligned16(d.dst) && aligned16(d.a);
             const int burst = two_input_burst_rows(delta_dtype, merged_dtype, vector_ok ? vec : 1);
-            if ((rc = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(g_retrieve_rows, burst)))) return rc;
+            const StreamBytes eb{ elem_bytes(merged_dtype), elem_bytes(delta_dtype), 0, 0 };
+            if ((rc = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(g_retrieve_rows, burst), eb))) return rc;
         }
         CachedPlan fresh;
         fresh.key = key;
@@ -611,7 +648,7 @@ int randes_delta_stats(const randes_layer *layers, int32_t n_layers,
     if ((rc = current_device(&dev))) return rc;
     std::lock_guard<std::mutex> lock(g_mu);
     std::string key;
-    const int32_t head[4] = { PLAN_STATS, n_layers, (int32_t)dtype, g_retrieve_rows * 4 + g_max_wx_shift };
+    const int32_t head[4] = { PLAN_STATS, n_layers, (int32_t)dtype, knob_word(g_retrieve_rows) };
     append(&key, head, sizeof(head));
     append(&key, layers, sizeof(randes_layer) * (size_t)n_layers);
     append(&key, delta_a, sizeof(void *) * (size_t)n_layers);
@@ -636,7 +673,8 @@ int randes_delta_stats(const randes_layer *layers, int32_t n_layers,
             d.flip = (layers[l].flags & RANDES_FLIP) ? 1u : 0u;
             const bool vector_ok = (layers[l].cols % vec) == 0 && aligned16(d.a) && aligned16(d.b);
             const int burst = two_input_burst_rows(dtype, dtype, vector_ok ? vec : 1);
-            if ((rc = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(g_retrieve_rows, burst)))) return rc;
+            const StreamBytes eb{ 0, elem_bytes(dtype), elem_bytes(dtype), 0 };
+            if ((rc = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(g_retrieve_rows, burst), eb))) return rc;
         }
         hp.extra_bytes = ((size_t)hp.vec.n_tiles + hp.scl.n_tiles) * 3 * sizeof(double);
         CachedPlan fresh;
@@ -874,6 +912,13 @@ int randes_set_tile_cols(int32_t max_waves_along_columns)
     }
     std::lock_guard<std::mutex> lock(g_mu);
     g_max_wx_shift = shift;
+    return RANDES_OK;
+}
+
+int randes_set_fold(int32_t enable)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    g_fold = enable ? 1 : 0;
     return RANDES_OK;
 }
 

@@ -244,7 +244,9 @@ __device__ __forceinline__ uint32_t stage_sign_bits(uint32_t *sbits, const Tile 
         for (uint32_t q = threadIdx.x; q < n_keys * nblk; q += WG) {
             const uint32_t i = q / nblk, blk = q % nblk;
             const uint32_t klo = keys ? keys[2 * i] : key_lo, khi = keys ? keys[2 * i + 1] : key_hi;
-            const u32x4_t o = sign_block(klo, khi, t.L.layer_id, (t.tile_col0 >> 7) + blk);
+            uint32_t gen_blk = (t.tile_col0 >> 7) + blk;
+            if (t.L.sign_blocks) gen_blk %= t.L.sign_blocks;   // folded rows: the pattern of one row repeats
+            const u32x4_t o = sign_block(klo, khi, t.L.layer_id, gen_blk);
             uint32_t *w = sbits + (size_t)q * 4u;
             w[0] = o.w[0]; w[1] = o.w[1]; w[2] = o.w[2]; w[3] = o.w[3];
         }

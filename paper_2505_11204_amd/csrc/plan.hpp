@@ -25,6 +25,8 @@ struct LayerDev {
     uint32_t tile_rows; // rows per tile
     uint32_t wx;        // waves of a workgroup laid along the columns (1, 2 or 4)
     uint32_t wx_shift;  // log2(wx)
+    uint32_t sign_blocks;  // 0, or: this descriptor shows several rows of the layer as one (rows folded),
+                           // and the sign pattern repeats every sign_blocks generator blocks of 128 columns
 };
 
 // What a streaming kernel receives by value.
@@ -76,6 +78,13 @@ void layer_perm(uint64_t seed, int32_t group, int32_t group_size, int32_t *perm_
 // `vec` columns each and waves that own `rows_per_wave` rows of a tile; returns
 // the layer's tile count, or 0 if the layer is too wide for 32-bit in-tile offsets.
 uint64_t plan_layer_geometry(LayerDev *d, int vec, int rows_per_wave, int max_wx_shift = 2);
+
+// How many consecutive rows of a rows x cols layer to show to the kernels as one row, so that fewer
+// lanes of the 64 * vec * {1, 2, 4} column wide tiles hang over the end of a row (768 bf16 columns
+// leave a quarter of the lanes idle; two rows = 1536 columns leave none).  1 = leave the layer as it
+// is.  Folding needs cols to be a multiple of 128, the generator's block, so that a block of the
+// folded row is a whole block of the sign pattern.
+int fold_factor(int64_t rows, int64_t cols, int vec, int max_wx_shift = 2);
 
 // coarse[i] = layer holding tile 1024 * i, for i = 0 .. ceil(n_tiles / 1024).
 void build_coarse_index(SubPlan *sp);

@@ -653,3 +653,62 @@ def test_random_stacks_through_every_streaming_entry_point(trial):
     ow = oracle.merge_weights(layers, [np_lists(w) for w in weights], np_lists(base), seeds, CODE[d_in], CODE[d_merged])
     for l in range(len(stack)):
         compare(gw[l], ow[l], "trial %d merge from weights, layer %d" % (trial, l))
+
+
+def folding_stack():
+    """Layers whose rows are folded on the vector path (cols a multiple of 128 that leaves lanes of the
+    column tiles idle), with row counts that divide by the fold factor, leave a remainder, or are too
+    few to fold; groups of them are shuffled; one layer that never folds."""
+    return [
+        Layer(70, 768, 0, SRSF), Layer(70, 768, 0, SRSF), Layer(70, 768, 0, SRSF),
+        Layer(7, 384, 1, SRSF), Layer(7, 384, 1, SRSF),
+        Layer(1, 768, -1, FLIP), Layer(2, 640, -1, FLIP), Layer(3, 1152, -1, FLIP),
+        Layer(9, 11008, -1, FLIP), Layer(33, 2048, -1, FLIP), Layer(5, 896, -1, 0), Layer(11, 1664, -1, FLIP),
+    ]
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_folded_rows_match_the_oracle_and_the_unfolded_launch(dt):
+    stack = folding_stack()
+    layers = layers_of(stack)
+    K = 3
+    seeds = [3, (9 << 40) | 4, 5]
+    try:
+        rb.set_fold(True)
+        gm, om = run_both(stack, K, seeds, dt, dt, dt, dt, 0.75, [0, 2])
+        base, deltas = cpu_inputs(stack, K, dt)
+        g_base, g_d = to_gpu(base), [to_gpu(d) for d in deltas]
+        outs = rb.retrieve_many(layers, gm, g_base, [seeds[1], seeds[0]], [1.0, -0.5])
+        stats = rb.delta_stats(layers, g_d[0], seeds[0], g_d[1], seeds[1]).cpu().numpy()
+        weights = [[(b.float() + d.float()).to(TD[dt]) for b, d in zip(base, per)] for per in deltas]
+        gw = rb.merge_weights(layers, [to_gpu(w) for w in weights], g_base, seeds)
+        rb.update(layers, gm, g_d[1], seeds[1], remove=True)
+        # the same calls with folding off: identical bits
+        rb.set_fold(False)
+        gm2 = rb.merge(layers, g_d, seeds)
+        outs2 = rb.retrieve_many(layers, gm2, g_base, [seeds[1], seeds[0]], [1.0, -0.5])
+        stats2 = rb.delta_stats(layers, g_d[0], seeds[0], g_d[1], seeds[1]).cpu().numpy()
+        gw2 = rb.merge_weights(layers, [to_gpu(w) for w in weights], g_base, seeds)
+        rb.update(layers, gm2, g_d[1], seeds[1], remove=True)
+    finally:
+        rb.set_fold(True)
+    view = torch.int16 if dt == "bf16" else torch.int32
+    for l in range(len(stack)):
+        assert torch.equal(gm[l].view(view), gm2[l].view(view)), l
+        assert torch.equal(gw[l].view(view), gw2[l].view(view)), l
+        for q in range(2):
+            assert torch.equal(outs[q][l].view(view), outs2[q][l].view(view)), (q, l)
+    # the reduction's grouping changes with the tiling, its value to rounding does not
+    np.testing.assert_allclose(stats, stats2, rtol=1e-12)
+    for q, (sd, lam) in enumerate([(seeds[1], 1.0), (seeds[0], -0.5)]):
+        want = oracle.retrieve(layers, om, np_lists(base), sd, lam, CODE[dt], CODE[dt], CODE[dt])
+        for l in range(len(stack)):
+            compare(outs[q][l], want[l], "folded, request %d layer %d" % (q, l))
+    oracle.update(layers, om, np_lists(deltas[1]), seeds[1], True, CODE[dt], CODE[dt])
+    ow = oracle.merge_weights(layers, [np_lists(w) for w in weights], np_lists(base), seeds, CODE[dt], CODE[dt])
+    for l in range(len(stack)):
+        compare(gm[l], om[l], "folded, after removal, layer %d" % l)
+        compare(gw[l], ow[l], "folded, merge from weights, layer %d" % l)
+    a = np.concatenate([x.astype(np.float64).ravel() for x in oracle.merge(layers, [np_lists(deltas[0])], [seeds[0]], CODE[dt], 0)])
+    b = np.concatenate([x.astype(np.float64).ravel() for x in oracle.merge(layers, [np_lists(deltas[1])], [seeds[1]], CODE[dt], 0)])
+    np.testing.assert_allclose(stats, [a @ b, a @ a, b @ b], rtol=1e-10)
