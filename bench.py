@@ -64,6 +64,7 @@ def parse():
                     help="groups: find the memory's address groups by timing copies and place read and "
                          "write streams in different ones (stacks of 8 GiB and more); plain: one "
                          "allocation per stack, wherever the allocator puts it")
+    ap.add_argument("--tasks", type=int, default=0, help="number of merged models (0 = the workload's own)")
     ap.add_argument("--no-fold", action="store_true",
                     help="hand every layer to the kernels row by row (see randes_set_fold)")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the plain-streaming probe")
@@ -266,6 +267,8 @@ def main():
     stack_fn, dtype, K, n_req, delta_std, scaled = WORKLOADS[args.workload]
     if args.requests:
         n_req = args.requests
+    if args.tasks:
+        K = args.tasks
     stack = stack_fn()
     layers = [(l.rows, l.cols, l.group, l.flags) for l in stack]
     n_elem = wl.n_elements(stack)
