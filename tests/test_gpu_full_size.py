@@ -207,3 +207,46 @@ def test_llama_7b_four_models_in_one_pass_sampled_rows():
         got = gather_rows(outs[q], rs)
         for l in range(len(stack)):
             _same_bits(got[l], want[l], "request %d layer %d" % (q, l))
+
+
+def test_llama_7b_in_the_benchmark_layout_sampled_rows():
+    # the stacks exactly where the benchmark puts them: one large allocation, cut by measured address
+    # groups (merged and base in one group, the output stack across a group boundary)
+    from paper_2505_11204_amd import placement
+    torch.cuda.empty_cache()
+    stack = wl.llama_7b()
+    layers = layers_of(stack)
+    K, dtype, td = 8, "bf16", torch.bfloat16
+    seeds = [42 + i for i in range(K)]
+    n = wl.stack_elements(stack, td)
+    free_bytes, _ = torch.cuda.mem_get_info()
+    arena = placement.Arena(free_bytes - (12 << 30))
+    labels = arena.classify()
+    layout = placement.plan_serving_layout(labels, arena.chunk_bytes, n * 2, K)
+    if layout is None:      # no usable groups on this machine: sequential placement in the same arena
+        step = (n * 2 + 255) // 256 * 256
+        layout = {"base": 0, "deltas": [(1 + i) * step for i in range(K)], "merged": (K + 1) * step,
+                  "out": (K + 2) * step}
+    base, deltas = wl.make_inputs(
+        stack, K, dtype=dtype, device="cuda", data_seed=1234, delta_std=5e-4,
+        place=lambda who: arena.flat(layout["base"] if who == "base" else layout["deltas"][who], n, td))
+    _, merged = wl.alloc_stack(stack, td, "cuda", into=arena.flat(layout["merged"], n, td))
+    _, out = wl.alloc_stack(stack, td, "cuda", into=arena.flat(layout["out"], n, td))
+    rb.merge(layers, deltas, seeds, merged=merged)
+    torch.cuda.synchronize()
+    rs = _row_sets(stack)
+    sh = _shadow(stack, rs)
+    want_m = oracle.merge(sh, [gather_rows(d, rs) for d in deltas], seeds, CODE[dtype], CODE[dtype], n_threads=8)
+    got_m = gather_rows(merged, rs)
+    for l in range(len(stack)):
+        _same_bits(got_m[l], want_m[l], "merged layer %d" % l)
+    sh_base = gather_rows(base, rs)
+    for i in (1, 6):
+        rb.retrieve(layers, merged, base, seeds[i], 1.0, out=out)
+        torch.cuda.synchronize()
+        want_o = oracle.retrieve(sh, want_m, sh_base, seeds[i], 1.0, CODE[dtype], CODE[dtype], CODE[dtype], n_threads=8)
+        got_o = gather_rows(out, rs)
+        for l in range(len(stack)):
+            _same_bits(got_o[l], want_o[l], "task %d layer %d" % (i, l))
+    del arena, base, deltas, merged, out
+    torch.cuda.empty_cache()
