@@ -612,7 +612,7 @@ def test_random_stacks_through_every_streaming_entry_point(trial):
     # counts, dtypes and scales; merge, retrieve, several retrievals per pass, hot add / remove and
     # merge-from-weights against the oracle
     rnd = np.random.RandomState(7000 + trial)
-    shapes = [(rnd.randint(1, 70), int(rnd.choice([1, 7, 8, 64, 130, 136, 520, 1032, 2056]))) for _ in range(3)]
+    shapes = [(rnd.randint(1, 70), int(rnd.choice([1, 7, 8, 64, 130, 136, 384, 520, 640, 768, 1032, 2056]))) for _ in range(3)]
     stack = []
     for _ in range(rnd.randint(1, 9)):
         g = int(rnd.randint(-1, 3))
