@@ -325,6 +325,34 @@ def test_lora_deltas_feed_the_merge_bit_exactly():
         compare(m[l], o_m[l], "lora merge %d" % l)
 
 
+def test_lora_then_merge_against_an_oracle_only_pipeline():
+    # the same two steps with nothing of the GPU in the oracle's inputs: float64 products rounded
+    # to bf16 on the host, merged by the oracle.  The GPU's deltas may differ from those by one
+    # bf16 unit each (its products are binary32 sums in the hardware's order), so the merged
+    # values agree to K such units plus the final rounding.
+    stack = [Layer(96, 520, 0, SRSF)] * 3 + [Layer(40, 264, -1, FLIP)]
+    layers = layers_of(stack)
+    K = 4
+    factors = wl.make_lora_factors(stack, list(range(len(stack))), K, rank=16, dtype="bf16", device="cuda")
+    seeds = [42 + i for i in range(K)]
+    deltas = [rb.lora_materialize_batched([f[0] for f in per], [f[1] for f in per], 1.0) for per in factors]
+    got = rb.merge(layers, deltas, seeds)
+    host_deltas, biggest = [], 0.0
+    for per in factors:
+        row = []
+        for (Bq, Aq) in per:
+            want, _ = oracle.lora(to_np(Bq), to_np(Aq), 1.0, 1)
+            biggest = max(biggest, float(np.abs(want).max()))
+            row.append(oracle.f32_to_bf16(want.astype(np.float32)))
+        host_deltas.append(row)
+    want_m = oracle.merge(layers, host_deltas, seeds, 1, 1, n_threads=8)
+    for l in range(len(stack)):
+        g = got[l].float().cpu().numpy().astype(np.float64)
+        w = oracle.bf16_to_f32(want_m[l]).astype(np.float64)
+        tol = K * 2.0 ** -7 * biggest + 2.0 ** -7 * np.abs(w)
+        assert (np.abs(g - w) <= tol).all(), (l, np.abs(g - w).max())
+
+
 @pytest.mark.parametrize("dt_ab,dt_out", [("bf16", "bf16"), ("bf16", "f32"), ("f32", "f32")])
 @pytest.mark.parametrize("rank,n_tasks", [(16, 8), (5, 3), (40, 2)])
 def test_fused_lora_merge(dt_ab, dt_out, rank, n_tasks):
