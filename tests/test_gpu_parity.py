@@ -742,3 +742,41 @@ def test_folded_rows_match_the_oracle_and_the_unfolded_launch(dt):
     a = np.concatenate([x.astype(np.float64).ravel() for x in oracle.merge(layers, [np_lists(deltas[0])], [seeds[0]], CODE[dt], 0)])
     b = np.concatenate([x.astype(np.float64).ravel() for x in oracle.merge(layers, [np_lists(deltas[1])], [seeds[1]], CODE[dt], 0)])
     np.testing.assert_allclose(stats, [a @ b, a @ a, b @ b], rtol=1e-10)
+
+
+def test_concurrent_callers_on_their_own_streams():
+    # several host threads, each with its own stream and output stack, share the library's table
+    # cache (more distinct calls than it holds, so tables are dropped and rebuilt meanwhile)
+    import threading
+    stack = aligned_stack()[:6]
+    layers = layers_of(stack)
+    K, dt = 3, "f32"
+    seeds = [21, 22, 23]
+    base, deltas = cpu_inputs(stack, K, dt)
+    g_merged = rb.merge(layers, [to_gpu(d) for d in deltas], seeds)
+    g_base = to_gpu(base)
+    torch.cuda.synchronize()
+    n_threads, n_calls = 4, 40
+    outs = [rb.alloc_like_layers(layers, torch.float32) for _ in range(n_threads)]
+    errors = []
+
+    def worker(w):
+        try:
+            s = torch.cuda.Stream()
+            for c in range(n_calls):
+                rb.retrieve(layers, g_merged, g_base, 5000 + 100 * w + c, 1.0, out=outs[w], stream=s)
+            s.synchronize()
+        except Exception as e:        # noqa: BLE001
+            errors.append(repr(e))
+    threads = [threading.Thread(target=worker, args=(w,)) for w in range(n_threads)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    torch.cuda.synchronize()
+    o_merged = oracle.merge(layers, [np_lists(d) for d in deltas], seeds, 0, 0)
+    for w in range(n_threads):
+        want = oracle.retrieve(layers, o_merged, np_lists(base), 5000 + 100 * w + n_calls - 1, 1.0, 0, 0, 0)
+        for l in range(len(stack)):
+            compare(outs[w][l], want[l], "thread %d layer %d" % (w, l))
