@@ -29,7 +29,9 @@
  *    host and uploads them synchronously (hipMalloc + hipMemcpy); a repeated
  *    call only launches kernels and may therefore be recorded into a HIP
  *    graph.  At most 64 argument sets stay cached; the least recently used
- *    one is dropped (hipFree, which waits for the device).
+ *    one is dropped (hipFree, which waits for the device).  Tables of a call
+ *    made while its stream was being captured are kept until
+ *    randes_shutdown(), because the graph's kernels point into them.
  *  - Layer pointers must be aligned to their element size (else RANDES_EINVAL).
  *    16-byte aligned layers whose cols is a multiple of 4 (f32) / 8 (bf16)
  *    take the vectorised kernels; anything else takes a slower element-wise

@@ -54,6 +54,7 @@ struct CachedPlan {
     int device = 0;
     void *blob = nullptr;     // device tables
     void *extra = nullptr;    // scratch inside the blob (stats partials)
+    bool pinned = false;      // recorded into a HIP graph: its tables must outlive the cache's turnover
     StreamArgs vec{}, scl{};
 };
 
@@ -190,11 +191,28 @@ int current_device(int *dev)
 CachedPlan *insert_plan(CachedPlan &&cp)
 {
     g_plans.push_front(std::move(cp));
-    while (g_plans.size() > MAX_PLANS) {
-        if (g_plans.back().blob) (void)hipFree(g_plans.back().blob);
-        g_plans.pop_back();
+    // drop the least recently used tables beyond the limit, but never those a graph refers to
+    size_t loose = 0;
+    for (const CachedPlan &p : g_plans) loose += p.pinned ? 0 : 1;
+    for (auto it = g_plans.end(); loose > MAX_PLANS && it != g_plans.begin();) {
+        --it;
+        if (it->pinned || it == g_plans.begin()) continue;
+        if (it->blob) (void)hipFree(it->blob);
+        it = g_plans.erase(it);
+        --loose;
     }
     return &g_plans.front();
+}
+
+// A call recorded into a graph is replayed with the same kernel arguments, which point into the
+// call's tables: keep them until randes_shutdown().
+void pin_if_capturing(CachedPlan *cp, void *hip_stream)
+{
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing((hipStream_t)hip_stream, &st) == hipSuccess && st == hipStreamCaptureStatusActive)
+        cp->pinned = true;
+    else
+        (void)hipGetLastError();
 }
 
 }  // namespace
@@ -318,6 +336,7 @@ int merge_impl(const randes_layer *layers, int32_t n_layers,
         if ((rc = upload(hp, n_tasks, &fresh))) return rc;
         cp = insert_plan(std::move(fresh));
     }
+    pin_if_capturing(cp, hip_stream);
     hipStream_t s = (hipStream_t)hip_stream;
     hipError_t e = base ? launch_merge_weights(cp->vec, 1, delta_dtype, merged_dtype, s)
                         : launch_merge(cp->vec, 1, delta_dtype, merged_dtype, s);
@@ -420,6 +439,7 @@ int randes_retrieve(const randes_layer *layers, int32_t n_layers,
         if ((rc = upload(hp, 1, &fresh))) return rc;
         cp = insert_plan(std::move(fresh));
     }
+    pin_if_capturing(cp, hip_stream);
     StreamArgs av = cp->vec, as = cp->scl;
     av.key_lo = as.key_lo = (uint32_t)(seed & 0xffffffffu);
     av.key_hi = as.key_hi = (uint32_t)(seed >> 32);
@@ -485,6 +505,7 @@ int retrieve_many_pass(const randes_layer *layers, int32_t n_layers, const void 
         if ((rc = upload(hp, q, &fresh))) return rc;
         cp = insert_plan(std::move(fresh));
     }
+    pin_if_capturing(cp, hip_stream);
     StreamArgs av = cp->vec;
     for (int32_t i = 0; i < q; ++i) av.lambdas[i] = lambdas[i];
     hipError_t e = launch_retrieve_many(av, dtype, (hipStream_t)hip_stream);
@@ -618,6 +639,7 @@ int randes_update(const randes_layer *layers, int32_t n_layers,
         if ((rc = upload(hp, 1, &fresh))) return rc;
         cp = insert_plan(std::move(fresh));
     }
+    pin_if_capturing(cp, hip_stream);
     StreamArgs av = cp->vec, as = cp->scl;
     av.key_lo = as.key_lo = (uint32_t)(seed & 0xffffffffu);
     av.key_hi = as.key_hi = (uint32_t)(seed >> 32);
@@ -683,6 +705,7 @@ int randes_delta_stats(const randes_layer *layers, int32_t n_layers,
         if ((rc = upload(hp, 1, &fresh))) return rc;
         cp = insert_plan(std::move(fresh));
     }
+    pin_if_capturing(cp, hip_stream);
     StreamArgs av = cp->vec, as = cp->scl;
     av.key_lo = as.key_lo = (uint32_t)(seed_a & 0xffffffffu);
     av.key_hi = as.key_hi = (uint32_t)(seed_a >> 32);
@@ -755,6 +778,7 @@ int run_lora(std::vector<LoraItem> &items, const std::vector<LoraSeg> &segs, int
         if (e != hipSuccess) { (void)hipFree(fresh.blob); return hip_fail(e, "hipMemcpy(lora tables)"); }
         cp = insert_plan(std::move(fresh));
     }
+    pin_if_capturing(cp, hip_stream);
     hipError_t e = launch_lora((const LoraItem *)cp->blob, (int32_t)items.size(),
                                (const LoraSeg *)((const char *)cp->blob + items_bytes),
                                (const uint32_t *)((const char *)cp->blob + items_bytes + segs_bytes), (uint32_t)tiles,

@@ -628,6 +628,18 @@ def test_cached_calls_can_be_captured_in_a_graph():
             assert torch.equal(merged[l].view(torch.int16), want_m[l].view(torch.int16)), (rnd, l)
             assert torch.equal(out[l].view(torch.int16), want_o[l].view(torch.int16)), (rnd, l)
         assert torch.equal(stats, want_s)
+    # tables of recorded calls survive the cache's turnover: 80 other calls, then one more replay
+    scratch = rb.alloc_like_layers(layers, TD[dt])
+    for s_ in range(80):
+        rb.retrieve(lt, t_m, t_b, 70000 + s_, 1.0, out=scratch)
+    torch.cuda.synchronize()
+    for t in merged + out:
+        t.zero_()
+    graph.replay()
+    torch.cuda.synchronize()
+    for l in range(len(stack)):
+        assert torch.equal(merged[l].view(torch.int16), want_m[l].view(torch.int16)), l
+        assert torch.equal(out[l].view(torch.int16), want_o[l].view(torch.int16)), l
     # and the eager result is the oracle's
     o_m = oracle.merge(layers, [[to_np(t) for t in per] for per in g_d], seeds, CODE[dt], CODE[dt], n_threads=8)
     for l in range(len(stack)):
