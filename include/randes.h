@@ -28,10 +28,16 @@
  *    then.  The first call with a given argument set builds its tables on the
  *    host and uploads them synchronously (hipMalloc + hipMemcpy); a repeated
  *    call only launches kernels and may therefore be recorded into a HIP
- *    graph.  At most 64 argument sets stay cached; the least recently used
- *    one is dropped (hipFree, which waits for the device).  Tables of a call
- *    made while its stream was being captured are kept until
- *    randes_shutdown(), because the graph's kernels point into them.
+ *    graph.  A first call made while its stream is being captured is refused
+ *    with RANDES_ENOTSUP before anything is enqueued (call once eagerly
+ *    first).  256 argument sets stay cached per process; beyond that the least
+ *    recently used one is dropped from the cache (its tables are released by
+ *    randes_shutdown(), never in the middle of a call).  Tables of a call made
+ *    while its stream was being captured are kept until randes_shutdown(),
+ *    because the graph's kernels point into them (at most 4096 such sets).
+ *  - Threads: every entry point may be called from several host threads at
+ *    once; the cache is locked only while a table set is looked up or added,
+ *    never across planning, uploads or launches.
  *  - Layer pointers must be aligned to their element size (else RANDES_EINVAL).
  *    16-byte aligned layers whose cols is a multiple of 4 (f32) / 8 (bf16)
  *    take the vectorised kernels; anything else takes a slower element-wise
@@ -57,8 +63,10 @@ typedef enum { RANDES_F32 = 0, RANDES_BF16 = 1 } randes_dtype;
 
 /* Per-layer flags.  FLIP: the layer takes the random sign flip D (Sec. 4.4).
  * SHUFFLE: the layer takes part in its group's random permutation (Sec. 4.3).
- * SHIFT: the group is instead shifted one position deeper with wrap-around
- * (App. "Dynamics between Layer Shuffling and Random Sign Flips").
+ * SHIFT: the group is rotated instead of shuffled, the layer-shifting variant of
+ * App. "Dynamics between Layer Shuffling and Random Sign Flips": model `seed`
+ * has every member moved (seed mod G) + 1 slots deeper, cyclically, so models
+ * with consecutive seeds lie one slot apart.
  * flags = 0 is the Identity context of Sec. "Impact of Context Matrix Design",
  * i.e. plain task arithmetic; choosing which layers carry flags realises the
  * ALL / MLP / ATTN target selection and the target-layer skip rate. */
@@ -180,8 +188,10 @@ int randes_update(const randes_layer *layers, int32_t n_layers,
  * identity || sum_j Delta_j ||^2 = sum_j ||Delta_j||^2 + 2 sum_{l<j} <Delta_l, Delta_j>.  Pass layers with
  * flags = 0 for the untransformed deltas.  The common factor D_i^-1 of a retrieval is orthogonal and
  * drops out of every inner product, so it is not needed here.  Work proceeds through per-workgroup
- * partial sums kept inside the cached tables and summed in a fixed order: the result is reproducible,
- * and two calls with identical arguments on different streams at the same time would race on them. */
+ * partial sums summed in a fixed order, so the result is reproducible.  The partial sums live beside
+ * the cached tables, one set per (argument set, stream): calls on one stream run in order, and equal
+ * calls on different streams do not share them.  (So the eager call that must precede recording this
+ * call into a graph has to be made on the stream that is then captured.) */
 int randes_delta_stats(const randes_layer *layers, int32_t n_layers,
                        const void *const *delta_a, uint64_t seed_a,
                        const void *const *delta_b, uint64_t seed_b,
@@ -230,32 +240,6 @@ const char *randes_strerror(int code);
 /* Free every cached descriptor table on every device.  The caller must have
  * synchronised all streams that ran library work.  Safe to call repeatedly. */
 int randes_shutdown(void);
-
-/* Launch-shape knobs for measurement: rows of a tile that one wavefront owns
- * (0 = built-in default, the kernels' burst size; larger values are clamped to
- * it).  Results never depend on them.  Returns RANDES_EINVAL for negative values. */
-int randes_set_tile_rows(int32_t merge_rows, int32_t retrieve_rows);
-
-/* Second launch-shape knob: how many of a workgroup's 4 wavefronts may sit side by
- * side along the columns (4, 2 or 1; 0 = default 4); the rest stack along the rows.
- * Results never depend on it. */
-int randes_set_tile_cols(int32_t max_waves_along_columns);
-
-/* Third launch-shape knob: a layer whose row length leaves lanes of the column tiles idle (768
- * bf16 columns: a quarter of them) is handed to the kernels with 2..8 consecutive rows shown as
- * one longer row (rows are contiguous in memory; the sign pattern of Sec. 4.4 then simply repeats
- * along the longer row).  enable = 0 switches this off (default on).  Results never depend on it. */
-int randes_set_fold(int32_t enable);
-
-/* Measurement aid, not part of the method: a plain streaming kernel with the same
- * launch shape as merge / retrieve and nothing else in it.  Reads n_inputs (1..8)
- * device streams of `bytes` bytes each (16-byte aligned, bytes a multiple of 16384)
- * and, if write != 0, stores their element-wise 32-bit integer sum to output
- * (bytes bytes); if write == 0 nothing is stored and output only needs 16 valid
- * bytes.  Its bandwidth is the machine's practical ceiling for that mix of reads
- * and writes, reported beside the method's kernels by the benchmark. */
-int randes_probe_stream(const void *const *inputs, int32_t n_inputs, void *output, int64_t bytes, int32_t write,
-                        void *hip_stream);
 
 #ifdef __cplusplus
 }

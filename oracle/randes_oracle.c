@@ -35,7 +35,7 @@
 
 #define ORACLE_FLIP 1    /* layer takes the random column sign flip   */
 #define ORACLE_SHUFFLE 2 /* layer takes part in its group's shuffle   */
-#define ORACLE_SHIFT 4   /* group is shifted one position deeper      */
+#define ORACLE_SHIFT 4   /* group is rotated deeper instead of shuffled */
 
 typedef struct {
     int64_t rows;  /* m */
@@ -170,9 +170,15 @@ static void store_elem(void *p, int64_t idx, int dtype, float v)
  * Delta_i^{k,j} <- Delta_i^{sigma_i^j(k), j}).  The members of group g are
  * the layers carrying that group id and the SHUFFLE (or SHIFT) flag, in
  * ascending layer order; everything else stays in place.  SHIFT replaces the
- * random permutation by the deterministic "one position deeper with
- * wrap-around" of App. "Dynamics between Layer Shuffling and Random Sign
- * Flips": slot (k+1) mod G receives layer k.
+ * random permutation by the deterministic layer shifting of App. "Dynamics
+ * between Layer Shuffling and Random Sign Flips" (every layer moves deeper,
+ * the deepest ones wrapping round to the front).  The appendix reports that
+ * shifting changes the cosine similarity among interfering deltas, which a
+ * rotation common to all models cannot do (it would only relabel the slots),
+ * so the distance depends on the model: model `seed` is rotated by
+ * d = (seed mod G) + 1 positions, taken mod G; slot (k + d) mod G receives
+ * layer k.  Seed 0 moves by one position and consecutive seeds (App. "Default
+ * Experimental Setup": global seed + model index) lie one position apart.
  * Returns 0, or -1 if members of one group differ in shape.
  * ---------------------------------------------------------------------- */
 int oracle_source_table(const oracle_layer *layers, int32_t n_layers,
@@ -201,7 +207,8 @@ int oracle_source_table(const oracle_layer *layers, int32_t n_layers,
         if (rc) break;
         for (int32_t i = 0; i < n_tasks; ++i) {
             if (shift) {
-                for (int32_t k = 0; k < G; ++k) perm[(k + 1) % G] = k;
+                int32_t d = (int32_t)((seeds[i] % (uint64_t)G + 1u) % (uint64_t)G);
+                for (int32_t k = 0; k < G; ++k) perm[(k + d) % G] = k;
             } else {
                 oracle_layer_perm(seeds[i], g, G, perm, NULL);
             }
@@ -299,8 +306,8 @@ int oracle_merge_weights(const oracle_layer *layers, int32_t n_layers,
 }
 
 /* ------------------------------------------------------------------------
- * retrieve (Sec. 4 eq. for hat Theta_i; Sec. 4.4 with D^{-1} = D; Sec. 4.3
- * "the inverse of the corresponding permutation"): slot l of the
+ * retrieve (Sec. 4 eq. for hat Theta_i; Sec. 4.4 with D^{-1} = D; Sec. 4.3:
+ * the model's permutation is undone): slot l of the
  * superposition goes back to layer t = src(l) of the requested model:
  *     out[t][r][c] = base[t][r][c] + lambda * ((-1)^{s(seed, l, c)} * Delta_*[l][r][c])
  * with a single rounding (fused multiply-add) in binary32.

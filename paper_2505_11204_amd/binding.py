@@ -22,11 +22,12 @@ MAX_TASKS = 128
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "librandes.so")
 
+# include/randes.h: the method's calls
 EXPORTS = ["randes_layer_perm", "randes_source_table", "randes_sign_mask", "randes_merge", "randes_merge_weights",
            "randes_retrieve", "randes_retrieve_many", "randes_update", "randes_delta_stats", "randes_lora_materialize",
-           "randes_lora_materialize_batched", "randes_lora_merge", "randes_strerror", "randes_shutdown",
-           "randes_set_tile_rows", "randes_set_tile_cols", "randes_set_fold",
-           "randes_probe_stream"]
+           "randes_lora_materialize_batched", "randes_lora_merge", "randes_strerror", "randes_shutdown"]
+# include/randes_bench.h: measurement aids
+BENCH_EXPORTS = ["randes_set_tile_rows", "randes_set_tile_cols", "randes_set_fold", "randes_probe_stream"]
 
 
 class RandesError(RuntimeError):
@@ -76,7 +77,7 @@ def lib():
     L.randes_set_tile_cols.argtypes = [i32]
     L.randes_set_fold.argtypes = [i32]
     L.randes_probe_stream.argtypes = [vp, i32, vp, i64, i32, vp]
-    for name in EXPORTS:
+    for name in EXPORTS + BENCH_EXPORTS:
         if name != "randes_strerror":
             getattr(L, name).restype = ctypes.c_int
     _lib = L
@@ -390,7 +391,7 @@ def lora_merge(layers, factors, seeds, scale=1.0, merged=None, merged_dtype=None
 
 
 def set_tile_rows(merge_rows=0, retrieve_rows=0):
-    """Launch-shape knob for measurements (0 = default).  Results do not depend on it."""
+    """Launch-shape knob of the calling thread for measurements (0 = default).  Results do not depend on it."""
     _check(lib().randes_set_tile_rows(int(merge_rows), int(retrieve_rows)))
 
 

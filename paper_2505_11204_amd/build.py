@@ -1,6 +1,6 @@
 """Build ``librandes.so`` (gfx950) in-tree with hipcc.
 
-``python -m paper_2505_11204_amd.build`` compiles the three sources under
+``python -m paper_2505_11204_amd.build`` compiles the sources under
 ``csrc/`` into ``paper_2505_11204_amd/librandes.so``.  hipcc cross-compiles, so
 no GPU is needed to build.
 """
@@ -12,7 +12,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librandes.so")
 SOURCES = ["kernels.hip", "lora.hip", "plan.cpp", "api.cpp"]
-HEADERS = ["launch.hpp", "plan.hpp", "philox.hpp", "device_util.hpp", os.path.join("..", "..", "include", "randes.h")]
+HEADERS = ["launch.hpp", "plan.hpp", "philox.hpp", "device_util.hpp", "api_internal.hpp",
+           os.path.join("..", "..", "include", "randes.h"), os.path.join("..", "..", "include", "randes_bench.h")]
 
 # -ffp-contract=off: the merge is adds only and the retrieve asks for its one fused
 # multiply-add explicitly, so nothing may be contracted behind the source's back.

@@ -7,18 +7,25 @@
 #include <cmath>
 #include <cstring>
 #include <list>
+#include <memory>
 #include <mutex>
 #include <string>
+#include <unordered_map>
 #include <vector>
 
+#include "../../include/randes_bench.h"
+#include "api_internal.hpp"
 #include "launch.hpp"
 #include "plan.hpp"
 
 using namespace randes;
 
-namespace {
+namespace randes {
 
+namespace {
 thread_local std::string g_detail;   // text of the last failure on this thread
+thread_local Knobs g_knobs;          // launch-shape knobs of this thread
+}  // namespace
 
 int fail(int code, const std::string &why)
 {
@@ -33,93 +40,242 @@ int hip_fail(hipError_t e, const char *what)
     return RANDES_EHIP;
 }
 
-bool dtype_ok(int d) { return d == RANDES_F32 || d == RANDES_BF16; }
-size_t elem_bytes(int d) { return d == RANDES_F32 ? 4 : 2; }
-bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
-bool elem_aligned(const void *p, int dtype) { return ((uintptr_t)p & (elem_bytes(dtype) - 1)) == 0; }
+Knobs &knobs() { return g_knobs; }
 
-int g_merge_rows = 0, g_retrieve_rows = 0;   // rows per wave per tile; 0 = the kernels' burst size
-int g_max_wx_shift = 2;   // widest tile: 4 waves side by side along the columns
-int g_fold = 1;           // 1: rows of layers that leave lanes idle are folded (see fold_factor)
-
-// The launch-shape knobs as one word of a plan's cache key.
-int32_t knob_word(int rows) { return rows * 16 + g_max_wx_shift * 2 + g_fold; }
-
-// A wave handles one burst of at most `burst` rows; the knob can only shrink it.
-int clamp_rows(int knob, int burst) { return (knob <= 0 || knob > burst) ? burst : knob; }
-
-// ------------------------------------------------------------------ plan cache
-struct CachedPlan {
-    std::string key;
-    int device = 0;
-    void *blob = nullptr;     // device tables
-    void *extra = nullptr;    // scratch inside the blob (stats partials)
-    bool pinned = false;      // recorded into a HIP graph: its tables must outlive the cache's turnover
-    StreamArgs vec{}, scl{};
-};
-
-std::mutex g_mu;
-std::list<CachedPlan> g_plans;           // most recently used first
-constexpr size_t MAX_PLANS = 64;
-
-void append(std::string *k, const void *p, size_t n) { k->append((const char *)p, n); }
-
-CachedPlan *lookup(const std::string &key, int device)
-{
-    for (auto it = g_plans.begin(); it != g_plans.end(); ++it) {
-        if (it->device == device && it->key == key) {
-            g_plans.splice(g_plans.begin(), g_plans, it);
-            return &g_plans.front();
-        }
-    }
-    return nullptr;
-}
-
-// Lay the host plan out in one blob, upload it, and fill the kernel arguments.
-int upload(HostPlan &hp, int n_tasks, CachedPlan *cp)
+void pack_tables(HostPlan &hp, std::vector<char> *image, TableLayout *lay)
 {
     auto pad = [](size_t x) { return (x + 255) & ~(size_t)255; };
     build_coarse_index(&hp.vec);
     build_coarse_index(&hp.scl);
     const SubPlan *sub[2] = { &hp.vec, &hp.scl };
-    size_t off_layers[2], off_srcs[2], off_tb[2], off_co[2], off = 0;
+    size_t off = 0;
     for (int s = 0; s < 2; ++s) {
-        off_layers[s] = off; off = pad(off + sub[s]->layers.size() * sizeof(LayerDev));
-        off_srcs[s] = off;   off = pad(off + sub[s]->srcs.size() * sizeof(void *));
-        off_tb[s] = off;     off = pad(off + sub[s]->tile_begin.size() * sizeof(uint32_t));
-        off_co[s] = off;     off = pad(off + sub[s]->coarse.size() * sizeof(uint32_t));
+        lay->layers[s] = off;     off = pad(off + sub[s]->layers.size() * sizeof(LayerDev));
+        lay->srcs[s] = off;       off = pad(off + sub[s]->srcs.size() * sizeof(void *));
+        lay->tile_begin[s] = off; off = pad(off + sub[s]->tile_begin.size() * sizeof(uint32_t));
+        lay->coarse[s] = off;     off = pad(off + sub[s]->coarse.size() * sizeof(uint32_t));
     }
-    const size_t off_keys = off;
+    lay->keys = off;
     off = pad(off + hp.keys.size() * sizeof(uint32_t));
-    const size_t off_extra = off;
+    lay->extra = off;   // last, so that an image can be shipped without its scratch
     off = pad(off + hp.extra_bytes);
-    std::vector<char> host(off, 0);
+    lay->total = off;
+    image->assign(lay->extra, 0);
+    char *host = image->data();
     for (int s = 0; s < 2; ++s) {
-        if (!sub[s]->layers.empty()) memcpy(host.data() + off_layers[s], sub[s]->layers.data(), sub[s]->layers.size() * sizeof(LayerDev));
-        if (!sub[s]->srcs.empty()) memcpy(host.data() + off_srcs[s], sub[s]->srcs.data(), sub[s]->srcs.size() * sizeof(void *));
-        if (!sub[s]->tile_begin.empty()) memcpy(host.data() + off_tb[s], sub[s]->tile_begin.data(), sub[s]->tile_begin.size() * sizeof(uint32_t));
-        memcpy(host.data() + off_co[s], sub[s]->coarse.data(), sub[s]->coarse.size() * sizeof(uint32_t));
+        if (!sub[s]->layers.empty()) memcpy(host + lay->layers[s], sub[s]->layers.data(), sub[s]->layers.size() * sizeof(LayerDev));
+        if (!sub[s]->srcs.empty()) memcpy(host + lay->srcs[s], sub[s]->srcs.data(), sub[s]->srcs.size() * sizeof(void *));
+        if (!sub[s]->tile_begin.empty()) memcpy(host + lay->tile_begin[s], sub[s]->tile_begin.data(), sub[s]->tile_begin.size() * sizeof(uint32_t));
+        memcpy(host + lay->coarse[s], sub[s]->coarse.data(), sub[s]->coarse.size() * sizeof(uint32_t));
     }
-    if (!hp.keys.empty()) memcpy(host.data() + off_keys, hp.keys.data(), hp.keys.size() * sizeof(uint32_t));
-    hipError_t e = hipMalloc(&cp->blob, off);
-    if (e != hipSuccess) return hip_fail(e, "hipMalloc(plan tables)");
-    e = hipMemcpy(cp->blob, host.data(), off, hipMemcpyHostToDevice);
-    if (e != hipSuccess) { (void)hipFree(cp->blob); cp->blob = nullptr; return hip_fail(e, "hipMemcpy(plan tables)"); }
-    cp->extra = hp.extra_bytes ? (char *)cp->blob + off_extra : nullptr;
-    StreamArgs *args[2] = { &cp->vec, &cp->scl };
+    if (!hp.keys.empty()) memcpy(host + lay->keys, hp.keys.data(), hp.keys.size() * sizeof(uint32_t));
+}
+
+void bind_tables(const void *dev_base, const TableLayout &lay, const HostPlan &hp, int n_tasks,
+                 StreamArgs *vec, StreamArgs *scl)
+{
+    const SubPlan *sub[2] = { &hp.vec, &hp.scl };
+    StreamArgs *args[2] = { vec, scl };
+    const char *b = (const char *)dev_base;
     for (int s = 0; s < 2; ++s) {
         StreamArgs &a = *args[s];
         memset(&a, 0, sizeof(a));
-        const char *b = (const char *)cp->blob;
-        a.layers = (const LayerDev *)(b + off_layers[s]);
-        a.srcs = (const void *const *)(b + off_srcs[s]);
-        a.tile_begin = (const uint32_t *)(b + off_tb[s]);
-        a.coarse = (const uint32_t *)(b + off_co[s]);
-        a.keys = (const uint32_t *)(b + off_keys);
+        a.layers = (const LayerDev *)(b + lay.layers[s]);
+        a.srcs = (const void *const *)(b + lay.srcs[s]);
+        a.tile_begin = (const uint32_t *)(b + lay.tile_begin[s]);
+        a.coarse = (const uint32_t *)(b + lay.coarse[s]);
+        a.keys = (const uint32_t *)(b + lay.keys);
         a.n_layers = (int32_t)sub[s]->layers.size();
         a.n_tasks = n_tasks;
         a.n_tiles = sub[s]->n_tiles;
     }
+}
+
+}  // namespace randes
+
+namespace {
+
+// A wave handles one burst of at most `burst` rows; the knob can only shrink it.
+int clamp_rows(int knob, int burst) { return (knob <= 0 || knob > burst) ? burst : knob; }
+
+// ------------------------------------------------------------------ plan cache
+// A call's device tables are found by what the call was given: the kind of call, the layer list,
+// every pointer and seed.  The arguments are hashed where they lie (no copy on the cached path) and
+// compared piece by piece on a hash match; the copy is made once, when the tables are built.
+struct CallKey {
+    struct Piece { const void *p; size_t n; };
+    Piece piece[10];
+    int n_pieces = 0;
+    void add(const void *p, size_t n) { piece[n_pieces++] = Piece{ p, n }; }
+    uint64_t hash() const
+    {
+        uint64_t h = 0x243f6a8885a308d3ull;
+        for (int q = 0; q < n_pieces; ++q) {
+            const unsigned char *b = (const unsigned char *)piece[q].p;
+            size_t n = piece[q].n;
+            h = (h ^ (uint64_t)n) * 0x9e3779b97f4a7c15ull;
+            for (; n >= 8; n -= 8, b += 8) {
+                uint64_t w;
+                memcpy(&w, b, 8);
+                h = (h ^ w) * 0x9e3779b97f4a7c15ull;
+                h ^= h >> 29;
+            }
+            uint64_t w = 0;
+            if (n) memcpy(&w, b, n);
+            h = (h ^ w) * 0x9e3779b97f4a7c15ull;
+            h ^= h >> 32;
+        }
+        return h;
+    }
+    size_t bytes() const { size_t t = 0; for (int q = 0; q < n_pieces; ++q) t += piece[q].n; return t; }
+    bool equals(const std::string &stored) const
+    {
+        if (stored.size() != bytes()) return false;
+        size_t off = 0;
+        for (int q = 0; q < n_pieces; ++q) {
+            if (memcmp(stored.data() + off, piece[q].p, piece[q].n) != 0) return false;
+            off += piece[q].n;
+        }
+        return true;
+    }
+    std::string str() const
+    {
+        std::string s;
+        s.reserve(bytes());
+        for (int q = 0; q < n_pieces; ++q) s.append((const char *)piece[q].p, piece[q].n);
+        return s;
+    }
+};
+
+struct CachedPlan {
+    std::string key;
+    uint64_t hash = 0;
+    int device = 0;
+    void *blob = nullptr;     // device tables
+    void *extra = nullptr;    // scratch inside the blob (stats partials)
+    bool pinned = false;      // recorded into a HIP graph: its tables must outlive the cache's turnover
+    StreamArgs vec{}, scl{};
+    size_t items_bytes = 0, segs_bytes = 0;   // LoRA launches: where the segment and coarse tables start
+};
+using PlanRef = std::shared_ptr<CachedPlan>;
+
+// g_mu guards the three containers below and the `pinned` flags, for the length of a lookup or
+// an insertion only: host planning, uploads and kernel launches all happen outside it.
+std::mutex g_mu;
+std::list<PlanRef> g_lru;                                                       // most recently used first
+std::unordered_multimap<uint64_t, std::list<PlanRef>::iterator> g_index;        // by hash of the call
+std::vector<void *> g_retired;    // tables of argument sets dropped from the cache; freed by randes_shutdown()
+size_t g_pinned = 0;
+constexpr size_t MAX_PLANS = 256;     // argument sets kept (beyond those recorded into graphs)
+constexpr size_t MAX_PINNED = 4096;   // argument sets recorded into graphs
+
+PlanRef lookup_locked(uint64_t h, const CallKey &k, int device)
+{
+    auto range = g_index.equal_range(h);
+    for (auto it = range.first; it != range.second; ++it) {
+        const PlanRef &p = *it->second;
+        if (p->device == device && k.equals(p->key)) {
+            g_lru.splice(g_lru.begin(), g_lru, it->second);
+            return p;
+        }
+    }
+    return nullptr;
+}
+
+void insert_locked(const PlanRef &p)
+{
+    g_lru.push_front(p);
+    g_index.emplace(p->hash, g_lru.begin());
+    // Drop the least recently used argument sets beyond the limit, never those a graph refers to.
+    // Their tables are not freed here (hipFree waits for the whole device and is not allowed while
+    // a stream is being captured; kernels already enqueued may still read them): they are retired
+    // and released by randes_shutdown().
+    size_t loose = g_lru.size() - g_pinned;
+    for (auto it = g_lru.end(); loose > MAX_PLANS && it != g_lru.begin();) {
+        --it;
+        if ((*it)->pinned || it == g_lru.begin()) continue;
+        auto range = g_index.equal_range((*it)->hash);
+        for (auto ix = range.first; ix != range.second; ++ix)
+            if (ix->second == it) { g_index.erase(ix); break; }
+        if ((*it)->blob) g_retired.push_back((*it)->blob);
+        it = g_lru.erase(it);
+        --loose;
+    }
+}
+
+bool stream_is_capturing(void *hip_stream)
+{
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing((hipStream_t)hip_stream, &st) == hipSuccess) return st == hipStreamCaptureStatusActive;
+    (void)hipGetLastError();
+    return false;
+}
+
+int current_device(int *dev)
+{
+    hipError_t e = hipGetDevice(dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    return RANDES_OK;
+}
+
+// The tables of the call described by `k`: cached, or built now by `build(CachedPlan *)`, which
+// plans on the host and uploads (and leaves no allocation behind when it fails).  A call recorded
+// into a graph is replayed with kernel arguments that point into its tables, so those are kept
+// until randes_shutdown(); the first call with an argument set allocates and copies synchronously
+// and is therefore refused while its stream is being captured.
+template <class Build>
+int find_or_build(const CallKey &k, void *hip_stream, PlanRef *out, Build build)
+{
+    int dev, rc;
+    if ((rc = current_device(&dev))) return rc;
+    const uint64_t h = k.hash();
+    const bool capturing = stream_is_capturing(hip_stream);
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        PlanRef p = lookup_locked(h, k, dev);
+        if (p) {
+            if (capturing && !p->pinned) {
+                if (g_pinned >= MAX_PINNED)
+                    return fail(RANDES_ENOTSUP, "too many argument sets recorded into graphs; randes_shutdown() releases them");
+                p->pinned = true;
+                ++g_pinned;
+            }
+            *out = p;
+            return RANDES_OK;
+        }
+    }
+    if (capturing)
+        return fail(RANDES_ENOTSUP, "the first call with an argument set uploads its tables and cannot be recorded: "
+                                    "call once eagerly before capturing the stream");
+    PlanRef fresh = std::make_shared<CachedPlan>();
+    fresh->key = k.str();
+    fresh->hash = h;
+    fresh->device = dev;
+    if ((rc = build(fresh.get()))) return rc;
+    std::lock_guard<std::mutex> lock(g_mu);
+    PlanRef p = lookup_locked(h, k, dev);
+    if (p) {   // another thread built the same tables meanwhile: use those
+        if (fresh->blob) g_retired.push_back(fresh->blob);
+        *out = p;
+        return RANDES_OK;
+    }
+    insert_locked(fresh);
+    *out = fresh;
+    return RANDES_OK;
+}
+
+// Lay the host plan out in one blob, upload it, and fill the kernel arguments.
+int upload(HostPlan &hp, int n_tasks, CachedPlan *cp)
+{
+    std::vector<char> image;
+    TableLayout lay;
+    pack_tables(hp, &image, &lay);
+    hipError_t e = hipMalloc(&cp->blob, lay.total);
+    if (e != hipSuccess) { cp->blob = nullptr; return hip_fail(e, "hipMalloc(plan tables)"); }
+    e = hipMemcpy(cp->blob, image.data(), image.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) { (void)hipFree(cp->blob); cp->blob = nullptr; return hip_fail(e, "hipMemcpy(plan tables)"); }
+    cp->extra = hp.extra_bytes ? (char *)cp->blob + lay.extra : nullptr;
+    bind_tables(cp->blob, lay, hp, n_tasks, &cp->vec, &cp->scl);
     return RANDES_OK;
 }
 
@@ -133,7 +289,8 @@ int place_piece(HostPlan *hp, LayerDev d, const void *const *srcs, int n_srcs, b
 int place(HostPlan *hp, LayerDev d, const void *const *srcs, int n_srcs, bool vector_ok, int vec, int rows_per_wave,
           const StreamBytes &eb)
 {
-    const int f = (vector_ok && g_fold) ? fold_factor(d.rows, d.cols, vec, g_max_wx_shift) : 1;
+    const Knobs &kn = knobs();
+    const int f = (vector_ok && kn.fold) ? fold_factor(d.rows, d.cols, vec, kn.max_wx_shift) : 1;
     if (f <= 1) return place_piece(hp, d, srcs, n_srcs, vector_ok, vec, rows_per_wave);
     const int64_t rows = d.rows, cols = d.cols;
     LayerDev fd = d;
@@ -156,7 +313,7 @@ int place(HostPlan *hp, LayerDev d, const void *const *srcs, int n_srcs, bool ve
 int place_piece(HostPlan *hp, LayerDev d, const void *const *srcs, int n_srcs, bool vector_ok, int vec, int rows_per_wave)
 {
     SubPlan &sp = vector_ok ? hp->vec : hp->scl;
-    const uint64_t tiles = plan_layer_geometry(&d, vector_ok ? vec : 1, rows_per_wave, g_max_wx_shift);
+    const uint64_t tiles = plan_layer_geometry(&d, vector_ok ? vec : 1, rows_per_wave, knobs().max_wx_shift);
     if (tiles == 0) return fail(RANDES_ENOTSUP, "layer too wide for 32-bit in-tile offsets");
     if ((uint64_t)sp.n_tiles + tiles >= ((uint64_t)1 << 31)) return fail(RANDES_ENOTSUP, "too many tiles for one launch");
     if (sp.tile_begin.empty()) sp.tile_begin.push_back(0);
@@ -181,38 +338,21 @@ bool overlap(std::vector<Span> spans)
     return false;
 }
 
-int current_device(int *dev)
+// True if any two of the spans overlap.
+bool any_overlap(std::vector<Span> spans)
 {
-    hipError_t e = hipGetDevice(dev);
-    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
-    return RANDES_OK;
-}
-
-CachedPlan *insert_plan(CachedPlan &&cp)
-{
-    g_plans.push_front(std::move(cp));
-    // drop the least recently used tables beyond the limit, but never those a graph refers to
-    size_t loose = 0;
-    for (const CachedPlan &p : g_plans) loose += p.pinned ? 0 : 1;
-    for (auto it = g_plans.end(); loose > MAX_PLANS && it != g_plans.begin();) {
-        --it;
-        if (it->pinned || it == g_plans.begin()) continue;
-        if (it->blob) (void)hipFree(it->blob);
-        it = g_plans.erase(it);
-        --loose;
+    std::sort(spans.begin(), spans.end(), [](const Span &a, const Span &b) { return a.lo < b.lo; });
+    uintptr_t hi = 0;
+    for (const Span &s : spans) {
+        if (s.lo < hi) return true;
+        hi = std::max(hi, s.hi);
     }
-    return &g_plans.front();
+    return false;
 }
 
-// A call recorded into a graph is replayed with the same kernel arguments, which point into the
-// call's tables: keep them until randes_shutdown().
-void pin_if_capturing(CachedPlan *cp, void *hip_stream)
+Span span_of(const void *p, size_t elems, int dtype, int tag)
 {
-    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing((hipStream_t)hip_stream, &st) == hipSuccess && st == hipStreamCaptureStatusActive)
-        cp->pinned = true;
-    else
-        (void)hipGetLastError();
+    return Span{ (uintptr_t)p, (uintptr_t)p + elems * elem_bytes(dtype), tag };
 }
 
 }  // namespace
@@ -271,39 +411,35 @@ int merge_impl(const randes_layer *layers, int32_t n_layers,
         if (!merged[l] || !elem_aligned(merged[l], merged_dtype) || (base && (!base[l] || !elem_aligned(base[l], delta_dtype))))
             return fail(RANDES_EINVAL, "NULL or misaligned merged or base pointer");
 
-    int dev;
-    if ((rc = current_device(&dev))) return rc;
-    std::lock_guard<std::mutex> lock(g_mu);
-    const int32_t tile_rows = knob_word(g_merge_rows);   // the knobs, for the cache key
-    std::string key;
-    const int32_t head[6] = { base ? PLAN_MERGE_WEIGHTS : PLAN_MERGE, n_layers, n_tasks, (int32_t)delta_dtype, (int32_t)merged_dtype, tile_rows };
-    append(&key, head, sizeof(head));
-    append(&key, layers, sizeof(randes_layer) * (size_t)n_layers);
-    append(&key, deltas, sizeof(void *) * (size_t)n_tasks * (size_t)n_layers);
-    append(&key, seeds, sizeof(uint64_t) * (size_t)n_tasks);
-    append(&key, merged, sizeof(void *) * (size_t)n_layers);
-    if (base) append(&key, base, sizeof(void *) * (size_t)n_layers);
+    const Knobs kn = knobs();
+    const int32_t head[6] = { base ? PLAN_MERGE_WEIGHTS : PLAN_MERGE, n_layers, n_tasks, (int32_t)delta_dtype,
+                              (int32_t)merged_dtype, kn.word(kn.merge_rows) };
+    CallKey key;
+    key.add(head, sizeof(head));
+    key.add(layers, sizeof(randes_layer) * (size_t)n_layers);
+    key.add(deltas, sizeof(void *) * (size_t)n_tasks * (size_t)n_layers);
+    key.add(seeds, sizeof(uint64_t) * (size_t)n_tasks);
+    key.add(merged, sizeof(void *) * (size_t)n_layers);
+    if (base) key.add(base, sizeof(void *) * (size_t)n_layers);
 
-    CachedPlan *cp = lookup(key, dev);
-    if (!cp) {
+    PlanRef cp;
+    rc = find_or_build(key, hip_stream, &cp, [&](CachedPlan *fresh) -> int {
         // the superposition must not overwrite its own inputs
         std::vector<Span> spans;
         for (int32_t l = 0; l < n_layers; ++l) {
             const size_t n = (size_t)layers[l].rows * (size_t)layers[l].cols;
-            spans.push_back({ (uintptr_t)merged[l], (uintptr_t)merged[l] + n * elem_bytes(merged_dtype), 0 });
-            for (int32_t i = 0; i < n_tasks; ++i) {
-                const void *p = deltas[(size_t)i * n_layers + l];
-                spans.push_back({ (uintptr_t)p, (uintptr_t)p + n * elem_bytes(delta_dtype), 1 });
-            }
-            if (base) spans.push_back({ (uintptr_t)base[l], (uintptr_t)base[l] + n * elem_bytes(delta_dtype), 1 });
+            spans.push_back(span_of(merged[l], n, merged_dtype, 0));
+            for (int32_t i = 0; i < n_tasks; ++i) spans.push_back(span_of(deltas[(size_t)i * n_layers + l], n, delta_dtype, 1));
+            if (base) spans.push_back(span_of(base[l], n, delta_dtype, 1));
         }
         if (overlap(spans)) return fail(RANDES_EINVAL, "merged overlaps an input");
 
         HostPlan hp;
+        std::string why2;
         std::vector<std::vector<int32_t>> src((size_t)n_tasks);
         for (int32_t i = 0; i < n_tasks; ++i) {
-            rc = build_source_table(layers, n_layers, seeds[i], &src[(size_t)i], &why);
-            if (rc) return fail(rc, why);
+            const int rc2 = build_source_table(layers, n_layers, seeds[i], &src[(size_t)i], &why2);
+            if (rc2) return fail(rc2, why2);
             hp.keys.push_back((uint32_t)(seeds[i] & 0xffffffffu));
             hp.keys.push_back((uint32_t)(seeds[i] >> 32));
         }
@@ -328,15 +464,12 @@ int merge_impl(const randes_layer *layers, int32_t n_layers,
             }
             const int burst = base ? merge_weights_burst_rows() : merge_burst_rows();
             const StreamBytes eb{ elem_bytes(merged_dtype), 0, 0, elem_bytes(delta_dtype) };
-            if ((rc = place(&hp, d, ptrs.data(), n_streams, vector_ok, vec, clamp_rows(g_merge_rows, burst), eb))) return rc;
+            const int rc2 = place(&hp, d, ptrs.data(), n_streams, vector_ok, vec, clamp_rows(kn.merge_rows, burst), eb);
+            if (rc2) return rc2;
         }
-        CachedPlan fresh;
-        fresh.key = key;
-        fresh.device = dev;
-        if ((rc = upload(hp, n_tasks, &fresh))) return rc;
-        cp = insert_plan(std::move(fresh));
-    }
-    pin_if_capturing(cp, hip_stream);
+        return upload(hp, n_tasks, fresh);
+    });
+    if (rc) return rc;
     hipStream_t s = (hipStream_t)hip_stream;
     hipError_t e = base ? launch_merge_weights(cp->vec, 1, delta_dtype, merged_dtype, s)
                         : launch_merge(cp->vec, 1, delta_dtype, merged_dtype, s);
@@ -366,8 +499,6 @@ int randes_merge_weights(const randes_layer *layers, int32_t n_layers,
     return merge_impl(layers, n_layers, weights, base, n_tasks, seeds, weight_dtype, merged, merged_dtype, hip_stream);
 }
 
-
-
 int randes_retrieve(const randes_layer *layers, int32_t n_layers,
                     const void *const *merged, randes_dtype merged_dtype,
                     const void *const *base, randes_dtype base_dtype,
@@ -385,38 +516,37 @@ int randes_retrieve(const randes_layer *layers, int32_t n_layers,
             !elem_aligned(base[l], base_dtype) || !elem_aligned(out[l], out_dtype))
             return fail(RANDES_EINVAL, "NULL or misaligned layer pointer");
 
-    int dev;
-    if ((rc = current_device(&dev))) return rc;
-    std::lock_guard<std::mutex> lock(g_mu);
-    const int32_t tile_rows = knob_word(g_retrieve_rows);   // the knobs, for the cache key
-    std::string key;
-    const int32_t head[6] = { PLAN_RETRIEVE, n_layers, (int32_t)merged_dtype, (int32_t)base_dtype, (int32_t)out_dtype, tile_rows };
-    append(&key, head, sizeof(head));
-    append(&key, layers, sizeof(randes_layer) * (size_t)n_layers);
-    append(&key, merged, sizeof(void *) * (size_t)n_layers);
-    append(&key, base, sizeof(void *) * (size_t)n_layers);
-    append(&key, out, sizeof(void *) * (size_t)n_layers);
-    append(&key, &seed, sizeof(seed));
+    const Knobs kn = knobs();
+    const int32_t head[6] = { PLAN_RETRIEVE, n_layers, (int32_t)merged_dtype, (int32_t)base_dtype, (int32_t)out_dtype,
+                              kn.word(kn.retrieve_rows) };
+    CallKey key;
+    key.add(head, sizeof(head));
+    key.add(layers, sizeof(randes_layer) * (size_t)n_layers);
+    key.add(merged, sizeof(void *) * (size_t)n_layers);
+    key.add(base, sizeof(void *) * (size_t)n_layers);
+    key.add(out, sizeof(void *) * (size_t)n_layers);
+    key.add(&seed, sizeof(seed));
 
-    CachedPlan *cp = lookup(key, dev);
-    if (!cp) {
+    PlanRef cp;
+    rc = find_or_build(key, hip_stream, &cp, [&](CachedPlan *fresh) -> int {
         std::vector<Span> a, b;
         for (int32_t l = 0; l < n_layers; ++l) {
             const size_t n = (size_t)layers[l].rows * (size_t)layers[l].cols;
-            a.push_back({ (uintptr_t)out[l], (uintptr_t)out[l] + n * elem_bytes(out_dtype), 0 });
-            a.push_back({ (uintptr_t)merged[l], (uintptr_t)merged[l] + n * elem_bytes(merged_dtype), 1 });
+            a.push_back(span_of(out[l], n, out_dtype, 0));
+            a.push_back(span_of(merged[l], n, merged_dtype, 1));
             if (out[l] != base[l] || out_dtype != base_dtype) {
-                b.push_back({ (uintptr_t)out[l], (uintptr_t)out[l] + n * elem_bytes(out_dtype), 0 });
-                b.push_back({ (uintptr_t)base[l], (uintptr_t)base[l] + n * elem_bytes(base_dtype), 1 });
+                b.push_back(span_of(out[l], n, out_dtype, 0));
+                b.push_back(span_of(base[l], n, base_dtype, 1));
             }
         }
         if (overlap(a)) return fail(RANDES_EINVAL, "out overlaps merged");
         if (overlap(b)) return fail(RANDES_EINVAL, "out partially overlaps base");
 
         HostPlan hp;
+        std::string why2;
         std::vector<int32_t> src;
-        rc = build_source_table(layers, n_layers, seed, &src, &why);
-        if (rc) return fail(rc, why);
+        const int rc2 = build_source_table(layers, n_layers, seed, &src, &why2);
+        if (rc2) return fail(rc2, why2);
         const int vec = retrieve_vec(merged_dtype, base_dtype);
         for (int32_t l = 0; l < n_layers; ++l) {
             const int32_t t = src[(size_t)l];
@@ -431,15 +561,12 @@ int randes_retrieve(const randes_layer *layers, int32_t n_layers,
             const bool vector_ok = (layers[l].cols % vec) == 0 && aligned16(d.dst) && aligned16(d.a) && aligned16(d.b);
             const int burst = two_input_burst_rows(merged_dtype, base_dtype, vector_ok ? vec : 1);
             const StreamBytes eb{ elem_bytes(out_dtype), elem_bytes(merged_dtype), elem_bytes(base_dtype), 0 };
-            if ((rc = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(g_retrieve_rows, burst), eb))) return rc;
+            const int rc3 = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(kn.retrieve_rows, burst), eb);
+            if (rc3) return rc3;
         }
-        CachedPlan fresh;
-        fresh.key = key;
-        fresh.device = dev;
-        if ((rc = upload(hp, 1, &fresh))) return rc;
-        cp = insert_plan(std::move(fresh));
-    }
-    pin_if_capturing(cp, hip_stream);
+        return upload(hp, 1, fresh);
+    });
+    if (rc) return rc;
     StreamArgs av = cp->vec, as = cp->scl;
     av.key_lo = as.key_lo = (uint32_t)(seed & 0xffffffffu);
     av.key_hi = as.key_hi = (uint32_t)(seed >> 32);
@@ -461,24 +588,24 @@ int retrieve_many_pass(const randes_layer *layers, int32_t n_layers, const void 
                        const void *const *base, int32_t q, const uint64_t *seeds, const float *lambdas,
                        void *const *outs, int dtype, void *hip_stream)
 {
-    int dev, rc;
-    if ((rc = current_device(&dev))) return rc;
-    std::lock_guard<std::mutex> lock(g_mu);
-    std::string key, why;
-    const int32_t head[5] = { PLAN_RETRIEVE_MANY, n_layers, dtype, q, knob_word(0) };
-    append(&key, head, sizeof(head));
-    append(&key, layers, sizeof(randes_layer) * (size_t)n_layers);
-    append(&key, merged, sizeof(void *) * (size_t)n_layers);
-    append(&key, base, sizeof(void *) * (size_t)n_layers);
-    append(&key, outs, sizeof(void *) * (size_t)n_layers * (size_t)q);
-    append(&key, seeds, sizeof(uint64_t) * (size_t)q);
+    const Knobs kn = knobs();
+    const int32_t head[5] = { PLAN_RETRIEVE_MANY, n_layers, dtype, q, kn.word(0) };
+    CallKey key;
+    key.add(head, sizeof(head));
+    key.add(layers, sizeof(randes_layer) * (size_t)n_layers);
+    key.add(merged, sizeof(void *) * (size_t)n_layers);
+    key.add(base, sizeof(void *) * (size_t)n_layers);
+    key.add(outs, sizeof(void *) * (size_t)n_layers * (size_t)q);
+    key.add(seeds, sizeof(uint64_t) * (size_t)q);
 
-    CachedPlan *cp = lookup(key, dev);
-    if (!cp) {
+    PlanRef cp;
+    int rc = find_or_build(key, hip_stream, &cp, [&](CachedPlan *fresh) -> int {
         HostPlan hp;
+        std::string why;
         std::vector<std::vector<int32_t>> src((size_t)q);
         for (int32_t i = 0; i < q; ++i) {
-            if ((rc = build_source_table(layers, n_layers, seeds[i], &src[(size_t)i], &why))) return fail(rc, why);
+            const int rc2 = build_source_table(layers, n_layers, seeds[i], &src[(size_t)i], &why);
+            if (rc2) return fail(rc2, why);
             hp.keys.push_back((uint32_t)(seeds[i] & 0xffffffffu));
             hp.keys.push_back((uint32_t)(seeds[i] >> 32));
         }
@@ -497,32 +624,17 @@ int retrieve_many_pass(const randes_layer *layers, int32_t n_layers, const void 
                 ptrs[(size_t)(q + i)] = outs[(size_t)i * n_layers + t];
             }
             const StreamBytes eb{ 0, elem_bytes(dtype), 0, elem_bytes(dtype) };
-            if ((rc = place(&hp, d, ptrs.data(), 2 * q, true, vec, retrieve_many_rows(q), eb))) return rc;
+            const int rc2 = place(&hp, d, ptrs.data(), 2 * q, true, vec, retrieve_many_rows(q), eb);
+            if (rc2) return rc2;
         }
-        CachedPlan fresh;
-        fresh.key = key;
-        fresh.device = dev;
-        if ((rc = upload(hp, q, &fresh))) return rc;
-        cp = insert_plan(std::move(fresh));
-    }
-    pin_if_capturing(cp, hip_stream);
+        return upload(hp, q, fresh);
+    });
+    if (rc) return rc;
     StreamArgs av = cp->vec;
     for (int32_t i = 0; i < q; ++i) av.lambdas[i] = lambdas[i];
     hipError_t e = launch_retrieve_many(av, dtype, (hipStream_t)hip_stream);
     if (e != hipSuccess) return hip_fail(e, "retrieve (several models) launch");
     return RANDES_OK;
-}
-
-// True if any two of the spans overlap.
-bool any_overlap(std::vector<Span> spans)
-{
-    std::sort(spans.begin(), spans.end(), [](const Span &a, const Span &b) { return a.lo < b.lo; });
-    uintptr_t hi = 0;
-    for (const Span &s : spans) {
-        if (s.lo < hi) return true;
-        hi = std::max(hi, s.hi);
-    }
-    return false;
 }
 
 }  // namespace
@@ -550,13 +662,13 @@ int randes_retrieve_many(const randes_layer *layers, int32_t n_layers,
         if (!merged[l] || !base[l] || !elem_aligned(merged[l], merged_dtype) || !elem_aligned(base[l], base_dtype))
             return fail(RANDES_EINVAL, "NULL or misaligned layer pointer");
         const size_t n = (size_t)layers[l].rows * (size_t)layers[l].cols;
-        both.push_back({ (uintptr_t)merged[l], (uintptr_t)merged[l] + n * elem_bytes(merged_dtype), 1 });
-        both.push_back({ (uintptr_t)base[l], (uintptr_t)base[l] + n * elem_bytes(base_dtype), 1 });
+        both.push_back(span_of(merged[l], n, merged_dtype, 1));
+        both.push_back(span_of(base[l], n, base_dtype, 1));
         vector_ok = vector_ok && (layers[l].cols % vec) == 0 && aligned16(merged[l]) && aligned16(base[l]);
         for (int32_t q = 0; q < n_requests; ++q) {
             void *o = outs[(size_t)q * n_layers + l];
             if (!o || !elem_aligned(o, out_dtype)) return fail(RANDES_EINVAL, "NULL or misaligned output pointer");
-            out_spans.push_back({ (uintptr_t)o, (uintptr_t)o + n * elem_bytes(out_dtype), 0 });
+            out_spans.push_back(span_of(o, n, out_dtype, 0));
             both.push_back(out_spans.back());
             vector_ok = vector_ok && aligned16(o);
         }
@@ -594,31 +706,29 @@ int randes_update(const randes_layer *layers, int32_t n_layers,
         if (!merged[l] || !delta[l] || !elem_aligned(merged[l], merged_dtype) || !elem_aligned(delta[l], delta_dtype))
             return fail(RANDES_EINVAL, "NULL or misaligned layer pointer");
 
-    int dev;
-    if ((rc = current_device(&dev))) return rc;
-    std::lock_guard<std::mutex> lock(g_mu);
-    const int32_t tile_rows = knob_word(g_retrieve_rows);   // the knobs, for the cache key
-    std::string key;
-    const int32_t head[5] = { PLAN_UPDATE, n_layers, (int32_t)merged_dtype, (int32_t)delta_dtype, tile_rows };
-    append(&key, head, sizeof(head));
-    append(&key, layers, sizeof(randes_layer) * (size_t)n_layers);
-    append(&key, merged, sizeof(void *) * (size_t)n_layers);
-    append(&key, delta, sizeof(void *) * (size_t)n_layers);
-    append(&key, &seed, sizeof(seed));
+    const Knobs kn = knobs();
+    const int32_t head[5] = { PLAN_UPDATE, n_layers, (int32_t)merged_dtype, (int32_t)delta_dtype, kn.word(kn.retrieve_rows) };
+    CallKey key;
+    key.add(head, sizeof(head));
+    key.add(layers, sizeof(randes_layer) * (size_t)n_layers);
+    key.add(merged, sizeof(void *) * (size_t)n_layers);
+    key.add(delta, sizeof(void *) * (size_t)n_layers);
+    key.add(&seed, sizeof(seed));
 
-    CachedPlan *cp = lookup(key, dev);
-    if (!cp) {
+    PlanRef cp;
+    rc = find_or_build(key, hip_stream, &cp, [&](CachedPlan *fresh) -> int {
         std::vector<Span> spans;
         for (int32_t l = 0; l < n_layers; ++l) {
             const size_t n = (size_t)layers[l].rows * (size_t)layers[l].cols;
-            spans.push_back({ (uintptr_t)merged[l], (uintptr_t)merged[l] + n * elem_bytes(merged_dtype), 0 });
-            spans.push_back({ (uintptr_t)delta[l], (uintptr_t)delta[l] + n * elem_bytes(delta_dtype), 1 });
+            spans.push_back(span_of(merged[l], n, merged_dtype, 0));
+            spans.push_back(span_of(delta[l], n, delta_dtype, 1));
         }
         if (overlap(spans)) return fail(RANDES_EINVAL, "merged overlaps delta");
         HostPlan hp;
+        std::string why2;
         std::vector<int32_t> src;
-        rc = build_source_table(layers, n_layers, seed, &src, &why);
-        if (rc) return fail(rc, why);
+        const int rc2 = build_source_table(layers, n_layers, seed, &src, &why2);
+        if (rc2) return fail(rc2, why2);
         const int vec = update_vec(merged_dtype, delta_dtype);
         for (int32_t l = 0; l < n_layers; ++l) {
             LayerDev d{};
@@ -631,15 +741,12 @@ int randes_update(const randes_layer *layers, int32_t n_layers,
             const bool vector_ok = (layers[l].cols % vec) == 0 && aligned16(d.dst) && aligned16(d.a);
             const int burst = two_input_burst_rows(delta_dtype, merged_dtype, vector_ok ? vec : 1);
             const StreamBytes eb{ elem_bytes(merged_dtype), elem_bytes(delta_dtype), 0, 0 };
-            if ((rc = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(g_retrieve_rows, burst), eb))) return rc;
+            const int rc3 = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(kn.retrieve_rows, burst), eb);
+            if (rc3) return rc3;
         }
-        CachedPlan fresh;
-        fresh.key = key;
-        fresh.device = dev;
-        if ((rc = upload(hp, 1, &fresh))) return rc;
-        cp = insert_plan(std::move(fresh));
-    }
-    pin_if_capturing(cp, hip_stream);
+        return upload(hp, 1, fresh);
+    });
+    if (rc) return rc;
     StreamArgs av = cp->vec, as = cp->scl;
     av.key_lo = as.key_lo = (uint32_t)(seed & 0xffffffffu);
     av.key_hi = as.key_hi = (uint32_t)(seed >> 32);
@@ -652,13 +759,15 @@ int randes_update(const randes_layer *layers, int32_t n_layers,
     return RANDES_OK;
 }
 
-int randes_delta_stats(const randes_layer *layers, int32_t n_layers,
-                       const void *const *delta_a, uint64_t seed_a,
-                       const void *const *delta_b, uint64_t seed_b,
-                       randes_dtype dtype, double *out3, void *hip_stream)
+}  // extern "C"
+
+namespace randes {
+
+int validate_stats_args(const randes_layer *layers, int32_t n_layers,
+                        const void *const *delta_a, const void *const *delta_b, int dtype, const double *out3)
 {
     std::string why;
-    int rc = validate_layers(layers, n_layers, &why);
+    const int rc = validate_layers(layers, n_layers, &why);
     if (rc) return fail(rc, why);
     if (!delta_a || !delta_b || !out3) return fail(RANDES_EINVAL, "delta_a, delta_b or out3 is NULL");
     if (!dtype_ok(dtype)) return fail(RANDES_EINVAL, "unknown dtype");
@@ -666,46 +775,70 @@ int randes_delta_stats(const randes_layer *layers, int32_t n_layers,
         if (!delta_a[l] || !delta_b[l] || !elem_aligned(delta_a[l], dtype) || !elem_aligned(delta_b[l], dtype))
             return fail(RANDES_EINVAL, "NULL or misaligned layer pointer");
     if (((uintptr_t)out3 & 7u) != 0) return fail(RANDES_EINVAL, "out3 is not 8-byte aligned");
-    int dev;
-    if ((rc = current_device(&dev))) return rc;
-    std::lock_guard<std::mutex> lock(g_mu);
-    std::string key;
-    const int32_t head[4] = { PLAN_STATS, n_layers, (int32_t)dtype, knob_word(g_retrieve_rows) };
-    append(&key, head, sizeof(head));
-    append(&key, layers, sizeof(randes_layer) * (size_t)n_layers);
-    append(&key, delta_a, sizeof(void *) * (size_t)n_layers);
-    append(&key, delta_b, sizeof(void *) * (size_t)n_layers);
-    append(&key, &seed_a, sizeof(seed_a));
-    append(&key, &seed_b, sizeof(seed_b));
+    return RANDES_OK;
+}
 
-    CachedPlan *cp = lookup(key, dev);
-    if (!cp) {
-        HostPlan hp;
-        std::vector<int32_t> sa, sb;
-        if ((rc = build_source_table(layers, n_layers, seed_a, &sa, &why))) return fail(rc, why);
-        if ((rc = build_source_table(layers, n_layers, seed_b, &sb, &why))) return fail(rc, why);
-        const int vec = stats_vec(dtype);
-        for (int32_t l = 0; l < n_layers; ++l) {
-            LayerDev d{};
-            d.a = delta_a[sa[(size_t)l]];
-            d.b = delta_b[sb[(size_t)l]];
-            d.rows = (int32_t)layers[l].rows;
-            d.cols = (int32_t)layers[l].cols;
-            d.layer_id = (uint32_t)l;
-            d.flip = (layers[l].flags & RANDES_FLIP) ? 1u : 0u;
-            const bool vector_ok = (layers[l].cols % vec) == 0 && aligned16(d.a) && aligned16(d.b);
-            const int burst = two_input_burst_rows(dtype, dtype, vector_ok ? vec : 1);
-            const StreamBytes eb{ 0, elem_bytes(dtype), elem_bytes(dtype), 0 };
-            if ((rc = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(g_retrieve_rows, burst), eb))) return rc;
-        }
-        hp.extra_bytes = ((size_t)hp.vec.n_tiles + hp.scl.n_tiles) * 3 * sizeof(double);
-        CachedPlan fresh;
-        fresh.key = key;
-        fresh.device = dev;
-        if ((rc = upload(hp, 1, &fresh))) return rc;
-        cp = insert_plan(std::move(fresh));
+int build_stats_plan(const randes_layer *layers, int32_t n_layers,
+                     const void *const *delta_a, uint64_t seed_a,
+                     const void *const *delta_b, uint64_t seed_b,
+                     int dtype, HostPlan *hp)
+{
+    std::string why;
+    int rc;
+    const Knobs kn = knobs();
+    std::vector<int32_t> sa, sb;
+    if ((rc = build_source_table(layers, n_layers, seed_a, &sa, &why))) return fail(rc, why);
+    if ((rc = build_source_table(layers, n_layers, seed_b, &sb, &why))) return fail(rc, why);
+    const int vec = stats_vec(dtype);
+    for (int32_t l = 0; l < n_layers; ++l) {
+        LayerDev d{};
+        d.a = delta_a[sa[(size_t)l]];
+        d.b = delta_b[sb[(size_t)l]];
+        d.rows = (int32_t)layers[l].rows;
+        d.cols = (int32_t)layers[l].cols;
+        d.layer_id = (uint32_t)l;
+        d.flip = (layers[l].flags & RANDES_FLIP) ? 1u : 0u;
+        const bool vector_ok = (layers[l].cols % vec) == 0 && aligned16(d.a) && aligned16(d.b);
+        const int burst = two_input_burst_rows(dtype, dtype, vector_ok ? vec : 1);
+        const StreamBytes eb{ 0, elem_bytes(dtype), elem_bytes(dtype), 0 };
+        if ((rc = place(hp, d, nullptr, 0, vector_ok, vec, clamp_rows(kn.retrieve_rows, burst), eb))) return rc;
     }
-    pin_if_capturing(cp, hip_stream);
+    hp->extra_bytes = ((size_t)hp->vec.n_tiles + hp->scl.n_tiles) * 3 * sizeof(double);
+    return RANDES_OK;
+}
+
+}  // namespace randes
+
+extern "C" {
+
+int randes_delta_stats(const randes_layer *layers, int32_t n_layers,
+                       const void *const *delta_a, uint64_t seed_a,
+                       const void *const *delta_b, uint64_t seed_b,
+                       randes_dtype dtype, double *out3, void *hip_stream)
+{
+    int rc = validate_stats_args(layers, n_layers, delta_a, delta_b, dtype, out3);
+    if (rc) return rc;
+    const Knobs kn = knobs();
+    // The per-workgroup partial sums live with the tables, and calls on one stream run in order:
+    // one set of tables per stream keeps equal calls on different streams apart.
+    const int32_t head[4] = { PLAN_STATS, n_layers, (int32_t)dtype, kn.word(kn.retrieve_rows) };
+    CallKey key;
+    key.add(head, sizeof(head));
+    key.add(layers, sizeof(randes_layer) * (size_t)n_layers);
+    key.add(delta_a, sizeof(void *) * (size_t)n_layers);
+    key.add(delta_b, sizeof(void *) * (size_t)n_layers);
+    key.add(&seed_a, sizeof(seed_a));
+    key.add(&seed_b, sizeof(seed_b));
+    key.add(&hip_stream, sizeof(hip_stream));
+
+    PlanRef cp;
+    rc = find_or_build(key, hip_stream, &cp, [&](CachedPlan *fresh) -> int {
+        HostPlan hp;
+        const int rc2 = build_stats_plan(layers, n_layers, delta_a, seed_a, delta_b, seed_b, dtype, &hp);
+        if (rc2) return rc2;
+        return upload(hp, 1, fresh);
+    });
+    if (rc) return rc;
     StreamArgs av = cp->vec, as = cp->scl;
     av.key_lo = as.key_lo = (uint32_t)(seed_a & 0xffffffffu);
     av.key_hi = as.key_hi = (uint32_t)(seed_a >> 32);
@@ -742,12 +875,17 @@ int run_lora(std::vector<LoraItem> &items, const std::vector<LoraSeg> &segs, int
         tiles += (uint64_t)it.tiles_x * (uint64_t)(((int64_t)it.rows + wg_rows - 1) / wg_rows);
         if (tiles >= ((uint64_t)1 << 31)) return fail(RANDES_ENOTSUP, "too many tiles for one launch");
     }
-    int dev, rc;
-    if ((rc = current_device(&dev))) return rc;
     const size_t items_bytes = (sizeof(LoraItem) * items.size() + 255) & ~(size_t)255;
     const size_t segs_bytes = (sizeof(LoraSeg) * segs.size() + 255) & ~(size_t)255;
-    std::vector<uint32_t> coarse;
-    {
+    const int32_t head[3] = { 100, (int32_t)items.size(), (int32_t)segs.size() };
+    CallKey key;
+    key.add(head, sizeof(head));
+    key.add(items.data(), sizeof(LoraItem) * items.size());
+    key.add(segs.data(), sizeof(LoraSeg) * segs.size());
+
+    PlanRef cp;
+    int rc = find_or_build(key, hip_stream, &cp, [&](CachedPlan *fresh) -> int {
+        std::vector<uint32_t> coarse;
         uint32_t item = 0;
         const uint64_t n_chunks = (tiles + 63) / 64;
         for (uint64_t i = 0; i <= n_chunks; ++i) {
@@ -755,30 +893,17 @@ int run_lora(std::vector<LoraItem> &items, const std::vector<LoraSeg> &segs, int
             while (item + 1 < items.size() && items[item + 1].tile_begin <= tile) ++item;
             coarse.push_back(item);
         }
-    }
-    std::string key;
-    const int32_t head[3] = { 100, (int32_t)items.size(), (int32_t)segs.size() };
-    append(&key, head, sizeof(head));
-    append(&key, items.data(), sizeof(LoraItem) * items.size());
-    append(&key, segs.data(), sizeof(LoraSeg) * segs.size());
-
-    std::lock_guard<std::mutex> lock(g_mu);
-    CachedPlan *cp = lookup(key, dev);
-    if (!cp) {
         std::vector<char> host(items_bytes + segs_bytes + coarse.size() * sizeof(uint32_t), 0);
         memcpy(host.data(), items.data(), sizeof(LoraItem) * items.size());
         memcpy(host.data() + items_bytes, segs.data(), sizeof(LoraSeg) * segs.size());
         memcpy(host.data() + items_bytes + segs_bytes, coarse.data(), coarse.size() * sizeof(uint32_t));
-        CachedPlan fresh;
-        fresh.key = key;
-        fresh.device = dev;
-        hipError_t e = hipMalloc(&fresh.blob, host.size());
-        if (e != hipSuccess) return hip_fail(e, "hipMalloc(lora tables)");
-        e = hipMemcpy(fresh.blob, host.data(), host.size(), hipMemcpyHostToDevice);
-        if (e != hipSuccess) { (void)hipFree(fresh.blob); return hip_fail(e, "hipMemcpy(lora tables)"); }
-        cp = insert_plan(std::move(fresh));
-    }
-    pin_if_capturing(cp, hip_stream);
+        hipError_t e = hipMalloc(&fresh->blob, host.size());
+        if (e != hipSuccess) { fresh->blob = nullptr; return hip_fail(e, "hipMalloc(lora tables)"); }
+        e = hipMemcpy(fresh->blob, host.data(), host.size(), hipMemcpyHostToDevice);
+        if (e != hipSuccess) { (void)hipFree(fresh->blob); fresh->blob = nullptr; return hip_fail(e, "hipMemcpy(lora tables)"); }
+        return RANDES_OK;
+    });
+    if (rc) return rc;
     hipError_t e = launch_lora((const LoraItem *)cp->blob, (int32_t)items.size(),
                                (const LoraSeg *)((const char *)cp->blob + items_bytes),
                                (const uint32_t *)((const char *)cp->blob + items_bytes + segs_bytes), (uint32_t)tiles,
@@ -803,6 +928,7 @@ int randes_lora_materialize_batched(int32_t n, const void *const *Bs, const void
     if (!std::isfinite(scale)) return fail(RANDES_EINVAL, "scale is not finite");
     std::vector<LoraItem> items((size_t)n);
     std::vector<LoraSeg> segs((size_t)n);
+    std::vector<Span> out_spans, both;
     for (int32_t q = 0; q < n; ++q) {
         if (!Bs[q] || !As[q] || !outs[q]) return fail(RANDES_EINVAL, "NULL matrix pointer");
         if (!elem_aligned(Bs[q], ab_dtype) || !elem_aligned(As[q], ab_dtype) || !elem_aligned(outs[q], out_dtype))
@@ -817,7 +943,14 @@ int randes_lora_materialize_batched(int32_t n, const void *const *Bs, const void
         LoraSeg &sg = segs[(size_t)q];
         memset(&sg, 0, sizeof(sg));
         sg.B = Bs[q]; sg.A = As[q];
+        out_spans.push_back(span_of(outs[q], (size_t)rows[q] * (size_t)cols[q], out_dtype, 0));
+        both.push_back(out_spans.back());
+        both.push_back(span_of(Bs[q], (size_t)rows[q] * (size_t)rank, ab_dtype, 1));
+        both.push_back(span_of(As[q], (size_t)rank * (size_t)cols[q], ab_dtype, 1));
     }
+    // workgroups read factors while others write outputs: nothing written may be a factor or another output
+    if (any_overlap(out_spans)) return fail(RANDES_EINVAL, "output matrices overlap each other");
+    if (overlap(both)) return fail(RANDES_EINVAL, "an output matrix overlaps a factor");
     return run_lora(items, segs, rank, scale, ab_dtype, out_dtype, hip_stream);
 }
 
@@ -837,8 +970,19 @@ int randes_lora_merge(const randes_layer *layers, int32_t n_layers,
     for (int64_t q = 0; q < (int64_t)n_tasks * n_layers; ++q)
         if (!Bs[q] || !As[q] || !elem_aligned(Bs[q], ab_dtype) || !elem_aligned(As[q], ab_dtype))
             return fail(RANDES_EINVAL, "NULL or misaligned factor pointer");
-    for (int32_t l = 0; l < n_layers; ++l)
+    std::vector<Span> out_spans, both;
+    for (int32_t l = 0; l < n_layers; ++l) {
         if (!merged[l] || !elem_aligned(merged[l], merged_dtype)) return fail(RANDES_EINVAL, "NULL or misaligned merged pointer");
+        const size_t rows = (size_t)layers[l].rows, cols = (size_t)layers[l].cols;
+        out_spans.push_back(span_of(merged[l], rows * cols, merged_dtype, 0));
+        both.push_back(out_spans.back());
+        for (int32_t i = 0; i < n_tasks; ++i) {
+            both.push_back(span_of(Bs[(size_t)i * n_layers + l], rows * (size_t)rank, ab_dtype, 1));
+            both.push_back(span_of(As[(size_t)i * n_layers + l], (size_t)rank * cols, ab_dtype, 1));
+        }
+    }
+    if (any_overlap(out_spans)) return fail(RANDES_EINVAL, "merged matrices overlap each other");
+    if (overlap(both)) return fail(RANDES_EINVAL, "a merged matrix overlaps a factor");
     std::vector<std::vector<int32_t>> src((size_t)n_tasks);
     for (int32_t i = 0; i < n_tasks; ++i) {
         rc = build_source_table(layers, n_layers, seeds[i], &src[(size_t)i], &why);
@@ -891,23 +1035,31 @@ int randes_shutdown(void)
 {
     std::lock_guard<std::mutex> lock(g_mu);
     int rc = RANDES_OK;
-    for (CachedPlan &cp : g_plans) {
-        if (cp.blob) {
-            hipError_t e = hipFree(cp.blob);
+    for (const PlanRef &cp : g_lru) {
+        if (cp->blob) {
+            hipError_t e = hipFree(cp->blob);
             if (e != hipSuccess) rc = hip_fail(e, "hipFree(plan tables)");
+            cp->blob = nullptr;
         }
     }
-    g_plans.clear();
+    for (void *blob : g_retired) {
+        hipError_t e = hipFree(blob);
+        if (e != hipSuccess) rc = hip_fail(e, "hipFree(retired plan tables)");
+    }
+    g_retired.clear();
+    g_index.clear();
+    g_lru.clear();
+    g_pinned = 0;
     return rc;
 }
 
+// ------------------------------------------------------------------ measurement aids (randes_bench.h)
 int randes_set_tile_rows(int32_t merge_rows, int32_t retrieve_rows)
 {
     if (merge_rows < 0 || retrieve_rows < 0 || merge_rows > (1 << 20) || retrieve_rows > (1 << 20))
         return fail(RANDES_EINVAL, "tile rows out of range");
-    std::lock_guard<std::mutex> lock(g_mu);
-    g_merge_rows = merge_rows;
-    g_retrieve_rows = retrieve_rows;
+    knobs().merge_rows = merge_rows;
+    knobs().retrieve_rows = retrieve_rows;
     return RANDES_OK;
 }
 
@@ -934,15 +1086,13 @@ int randes_set_tile_cols(int32_t max_waves_along_columns)
     case 1: shift = 0; break;
     default: return fail(RANDES_EINVAL, "max_waves_along_columns must be 0, 1, 2 or 4");
     }
-    std::lock_guard<std::mutex> lock(g_mu);
-    g_max_wx_shift = shift;
+    knobs().max_wx_shift = shift;
     return RANDES_OK;
 }
 
 int randes_set_fold(int32_t enable)
 {
-    std::lock_guard<std::mutex> lock(g_mu);
-    g_fold = enable ? 1 : 0;
+    knobs().fold = enable ? 1 : 0;
     return RANDES_OK;
 }
 

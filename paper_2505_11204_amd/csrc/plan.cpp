@@ -61,8 +61,11 @@ int build_source_table(const randes_layer *layers, int32_t n_layers, uint64_t se
         }
         perm.resize((size_t)G);
         if (shift) {
-            // one position deeper with wrap-around: slot k+1 receives layer k
-            for (int32_t k = 0; k < G; ++k) perm[(size_t)k] = (k + G - 1) % G;
+            // layer shifting: the whole group moves `dist` slots deeper, cyclically.  The distance is
+            // the model's own (one more than its seed, modulo the group size), so that two models are
+            // shifted against each other and not merely relabelled together.
+            const int32_t dist = (int32_t)((seed % (uint64_t)G + 1u) % (uint64_t)G);
+            for (int32_t k = 0; k < G; ++k) perm[(size_t)k] = (k + G - dist) % G;   // slot k receives layer k - dist
         } else {
             layer_perm(seed, kv.first, G, perm.data());
         }

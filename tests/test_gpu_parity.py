@@ -566,9 +566,9 @@ def test_plan_cache_eviction_and_reuse():
     g_base = to_gpu(base)
     out = rb.alloc_like_layers(layers, torch.float32)
     for rnd in range(2):
-        for s in range(80):           # 80 different seeds = 80 different source tables
+        for s in range(300):          # 300 different seeds = 300 different table sets; the cache keeps 256
             rb.retrieve(layers, g_merged, g_base, 1000 + s, 1.0, out=out)
-            if s in (0, 41, 79):
+            if s in (0, 141, 299):
                 want = oracle.retrieve(layers, o_merged, np_lists(base), 1000 + s, 1.0, 0, 0, 0)
                 for l in range(len(stack)):
                     compare(out[l], want[l], "round %d seed %d layer %d" % (rnd, s, l))
@@ -599,14 +599,18 @@ def test_cached_calls_can_be_captured_in_a_graph():
         rb.merge(lt, t_d, seeds, merged=t_m)
         rb.retrieve(lt, t_m, t_b, seeds[1], 0.5, out=t_o)
         rb.delta_stats(lt, t_d0, seeds[0], t_d1, seeds[1], out=stats)
-    run()                                   # builds and caches the tables
-    torch.cuda.synchronize()
     side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        run()                               # builds and caches the tables (the diagnostics' are per stream)
+    torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.stream(side):
         graph.capture_begin()
-        run()
-        graph.capture_end()
+        try:
+            run()
+        finally:
+            graph.capture_end()
     torch.cuda.synchronize()
     for rnd in range(3):
         # new data in the same buffers, eager result first
@@ -628,9 +632,9 @@ def test_cached_calls_can_be_captured_in_a_graph():
             assert torch.equal(merged[l].view(torch.int16), want_m[l].view(torch.int16)), (rnd, l)
             assert torch.equal(out[l].view(torch.int16), want_o[l].view(torch.int16)), (rnd, l)
         assert torch.equal(stats, want_s)
-    # tables of recorded calls survive the cache's turnover: 80 other calls, then one more replay
+    # tables of recorded calls survive the cache's turnover: 300 other calls, then one more replay
     scratch = rb.alloc_like_layers(layers, TD[dt])
-    for s_ in range(80):
+    for s_ in range(300):
         rb.retrieve(lt, t_m, t_b, 70000 + s_, 1.0, out=scratch)
     torch.cuda.synchronize()
     for t in merged + out:
@@ -756,9 +760,54 @@ def test_folded_rows_match_the_oracle_and_the_unfolded_launch(dt):
     np.testing.assert_allclose(stats, [a @ b, a @ a, b @ b], rtol=1e-10)
 
 
+def test_first_call_during_capture_is_refused_before_anything_is_recorded():
+    # a call whose tables are not cached yet would have to allocate and copy: under capture it returns
+    # RANDES_ENOTSUP and records nothing; after one eager call the same call records fine
+    stack = aligned_stack()[:3]
+    layers = layers_of(stack)
+    base, deltas = cpu_inputs(stack, 2, "f32")
+    g_d = [to_gpu(d) for d in deltas]
+    merged = rb.alloc_like_layers(layers, torch.float32)
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    counter = torch.zeros(8, device="cuda")
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        try:
+            counter.add_(1.0)              # so that the recorded graph is not empty
+            with pytest.raises(rb.RandesError) as err:
+                rb.merge(layers, g_d, [901, 902], merged=merged)
+        finally:
+            graph.capture_end()
+    assert err.value.code == -2 and "eagerly" in str(err.value)
+    torch.cuda.synchronize()
+    graph.replay()                         # the capture itself survived the refused call
+    torch.cuda.synchronize()
+    assert counter.tolist() == [1.0] * 8
+    want = rb.merge(layers, g_d, [901, 902], merged=merged)       # eager: builds the tables
+    torch.cuda.synchronize()
+    want = [t.clone() for t in want]
+    graph2 = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph2.capture_begin()
+        try:
+            rb.merge(layers, g_d, [901, 902], merged=merged)
+        finally:
+            graph2.capture_end()
+    for t in merged:
+        t.zero_()
+    torch.cuda.synchronize()
+    graph2.replay()
+    torch.cuda.synchronize()
+    for l in range(len(stack)):
+        assert torch.equal(merged[l], want[l]), l
+
+
 def test_concurrent_callers_on_their_own_streams():
     # several host threads, each with its own stream and output stack, share the library's table
-    # cache (more distinct calls than it holds, so tables are dropped and rebuilt meanwhile)
+    # cache: 320 distinct calls are live at once, more than the 256 it keeps, so table sets are dropped
+    # and rebuilt while other threads launch
     import threading
     stack = aligned_stack()[:6]
     layers = layers_of(stack)
@@ -768,15 +817,16 @@ def test_concurrent_callers_on_their_own_streams():
     g_merged = rb.merge(layers, [to_gpu(d) for d in deltas], seeds)
     g_base = to_gpu(base)
     torch.cuda.synchronize()
-    n_threads, n_calls = 4, 40
+    n_threads, n_calls = 4, 80
     outs = [rb.alloc_like_layers(layers, torch.float32) for _ in range(n_threads)]
     errors = []
 
     def worker(w):
         try:
             s = torch.cuda.Stream()
-            for c in range(n_calls):
-                rb.retrieve(layers, g_merged, g_base, 5000 + 100 * w + c, 1.0, out=outs[w], stream=s)
+            for rnd in range(2):
+                for c in range(n_calls):
+                    rb.retrieve(layers, g_merged, g_base, 5000 + 100 * w + c, 1.0, out=outs[w], stream=s)
             s.synchronize()
         except Exception as e:        # noqa: BLE001
             errors.append(repr(e))
@@ -792,3 +842,40 @@ def test_concurrent_callers_on_their_own_streams():
         want = oracle.retrieve(layers, o_merged, np_lists(base), 5000 + 100 * w + n_calls - 1, 1.0, 0, 0, 0)
         for l in range(len(stack)):
             compare(outs[w][l], want[l], "thread %d layer %d" % (w, l))
+
+
+def test_equal_delta_stats_calls_on_two_streams_do_not_share_partial_sums():
+    # two host threads issue the same diagnostics call (same stacks, same seeds), each on its own stream,
+    # many times over while the other runs: every result must be the one the call gives alone
+    import threading
+    stack = [Layer(900, 1032, 0, SRSF)] * 3 + [Layer(257, 136, -1, FLIP)]
+    layers = layers_of(stack)
+    _, deltas = cpu_inputs(stack, 2, "f32", delta_std=1.0)
+    ga, gb = to_gpu(deltas[0]), to_gpu(deltas[1])
+    alone = rb.delta_stats(layers, ga, 42, gb, 43).cpu().numpy()
+    want = np.array(oracle.delta_stats(layers, np_lists(deltas[0]), 42, np_lists(deltas[1]), 43, 0))
+    assert np.all(np.abs(alone - want) <= 1e-11 * np.sqrt(want[1] * want[2]))
+    n_calls = 200
+    results = [torch.zeros((n_calls, 3), dtype=torch.float64, device="cuda") for _ in range(2)]
+    errors = []
+    go = threading.Barrier(2)
+
+    def worker(w):
+        try:
+            s = torch.cuda.Stream()
+            go.wait()
+            for c in range(n_calls):
+                rb.delta_stats(layers, ga, 42, gb, 43, out=results[w][c], stream=s)
+            s.synchronize()
+        except Exception as e:        # noqa: BLE001
+            errors.append(repr(e))
+    threads = [threading.Thread(target=worker, args=(w,)) for w in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    torch.cuda.synchronize()
+    for w in range(2):
+        got = results[w].cpu().numpy()
+        assert np.array_equal(got.view(np.uint64), np.tile(alone.view(np.uint64), (n_calls, 1))), w

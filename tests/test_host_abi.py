@@ -22,13 +22,28 @@ def lib():
     return rb.lib()
 
 
-def test_library_exports_every_declared_symbol(lib):
-    header = open(os.path.join(ROOT, "include", "randes.h")).read()
+@pytest.mark.parametrize("header_name,exports", [("randes.h", rb.EXPORTS), ("randes_bench.h", rb.BENCH_EXPORTS)])
+def test_library_exports_every_declared_symbol(lib, header_name, exports):
+    header = open(os.path.join(ROOT, "include", header_name)).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(randes_[a-z_]+)\s*\(", header))
-    assert declared == set(rb.EXPORTS)
+    assert declared == set(exports)
     for name in declared:
         assert hasattr(lib, name), name
+
+
+def test_the_method_header_holds_only_calls_that_cite_the_paper():
+    # every declaration of randes.h is preceded by a comment naming the passage it implements (or, for the
+    # housekeeping calls, saying what they are); measurement aids live in randes_bench.h
+    header = open(os.path.join(ROOT, "include", "randes.h")).read()
+    for name in rb.BENCH_EXPORTS:
+        assert name not in header
+    for name in rb.EXPORTS:
+        if name in ("randes_strerror", "randes_shutdown", "randes_lora_materialize_batched", "randes_source_table"):
+            continue
+        decl = header.index("int %s(" % name)
+        comment = header.rfind("/*", 0, decl)
+        assert re.search(r"Sec\.|App\.", header[comment:decl]), name
 
 
 def test_layer_perm_matches_oracle(lib):
@@ -52,9 +67,11 @@ def test_source_table_matches_oracle_on_the_benchmark_stacks(lib, name):
 
 def test_source_table_skip_rate_and_shift(lib):
     layers = [(1, 4, 0, (wl.SRSF if k % 2 == 0 else 0)) for k in range(8)] + [(1, 4, 3, wl.SHIFT)] * 5
-    want = oracle.source_table(layers, [5])[0].tolist()
-    assert rb.source_table(layers, 5) == want
-    assert want[8:] == [12, 8, 9, 10, 11]
+    for seed in (5, 0, 1, 99, 2 ** 64 - 1, 42, 43):
+        want = oracle.source_table(layers, [seed])[0].tolist()
+        assert rb.source_table(layers, seed) == want
+    assert rb.source_table(layers, 5)[8:] == [12, 8, 9, 10, 11]
+    assert rb.source_table(layers, 1)[8:] == [11, 12, 8, 9, 10]
 
 
 def test_stack_sizes():
@@ -130,6 +147,20 @@ def test_bad_arguments_are_error_codes_not_crashes(lib):
     assert lib.randes_lora_merge(one, 1, ptr, ptr, 4, 1, seeds, ctypes.c_float(1.0), 0, odd, 0, None) == EINVAL
     assert lib.randes_lora_materialize(ctypes.c_void_p(0x1001), ptr, 4, 4, 2, ctypes.c_float(1.0), 1, ptr, 1, None) == EINVAL
     assert b"misaligned" in lib.randes_strerror(EINVAL)
+    # LoRA outputs that alias a factor or each other are refused before anything is launched
+    f1 = ctypes.c_float(1.0)
+    pB, pA = ctypes.c_void_p(0x10000), ctypes.c_void_p(0x20000)
+    assert lib.randes_lora_materialize(pB, pA, 4, 4, 2, f1, 0, pA, 0, None) == EINVAL          # out is A
+    assert b"overlaps a factor" in lib.randes_strerror(EINVAL)
+    assert lib.randes_lora_materialize(pB, pA, 4, 4, 2, f1, 0, ctypes.c_void_p(0x10000 + 16), 0, None) == EINVAL   # inside B
+    two_b, two_a = (ctypes.c_void_p * 2)(0x10000, 0x11000), (ctypes.c_void_p * 2)(0x20000, 0x21000)
+    dims = (ctypes.c_int64 * 2)(4, 4)
+    same_out = (ctypes.c_void_p * 2)(0x30000, 0x30000 + 32)       # second output starts inside the first (64 bytes)
+    assert lib.randes_lora_materialize_batched(2, two_b, two_a, dims, dims, 2, f1, 0, same_out, 0, None) == EINVAL
+    assert b"overlap each other" in lib.randes_strerror(EINVAL)
+    merged_is_b = (ctypes.c_void_p * 1)(0x10000)
+    assert lib.randes_lora_merge(one, 1, two_b, two_a, 2, 1, seeds, f1, 0, merged_is_b, 0, None) == EINVAL
+    assert b"overlaps a factor" in lib.randes_strerror(EINVAL)
     assert lib.randes_probe_stream(ptr, 0, ptr, 16384, 1, None) == EINVAL
     assert lib.randes_probe_stream(ptr, 9, ptr, 16384, 1, None) == EINVAL
     assert lib.randes_probe_stream(ptr, 1, ptr, 1000, 1, None) == EINVAL

@@ -143,17 +143,32 @@ def test_group_shape_mismatch_is_rejected():
         oracle.source_table([(2, 3, 0, SRSF), (3, 2, 0, SRSF)], [1])
 
 
-def test_unflagged_members_stay_in_place_and_shift_is_one_deeper():
+def test_unflagged_members_stay_in_place_and_shift_moves_each_model_by_its_own_distance():
     # skip-rate pattern: only every 2nd layer of the group is a target
     layers = [(1, 4, 0, SRSF if k % 2 == 0 else 0) for k in range(8)]
     src = oracle.source_table(layers, [5])[0]
     assert [src[k] for k in range(1, 8, 2)] == [1, 3, 5, 7]
     sigma = oracle.layer_perm(5, 0, 4)
     assert [src[k] for k in range(0, 8, 2)] == [2 * int(s) for s in sigma]
-    # shift: layer k lands in slot k+1, the last wraps to slot 0
+    # layer shifting (App. "Dynamics between Layer Shuffling and Random Sign Flips"): model `seed` moves
+    # (seed mod G) + 1 slots deeper, the deepest layers wrapping to the front.  Written out by hand, G = 5:
     layers = [(1, 4, 0, SHIFT)] * 5
-    src = oracle.source_table(layers, [5, 99])
-    assert src[0].tolist() == [4, 0, 1, 2, 3] and src[1].tolist() == [4, 0, 1, 2, 3]
+    src = oracle.source_table(layers, [0, 1, 5, 99, 2 ** 64 - 1])
+    assert src[0].tolist() == [4, 0, 1, 2, 3]     # seed 0: one slot deeper, the last layer wraps to slot 0
+    assert src[1].tolist() == [3, 4, 0, 1, 2]     # seed 1: two slots
+    assert src[2].tolist() == [4, 0, 1, 2, 3]     # seed 5 = 0 mod 5: one slot again
+    assert src[3].tolist() == [0, 1, 2, 3, 4]     # seed 99 = 4 mod 5: five slots = none
+    assert src[4].tolist() == [4, 0, 1, 2, 3]     # 2^64 - 1 = 0 mod 5
+    # a shift common to all models would only relabel the slots; per-model distances move two models
+    # against each other: retrieving model 0 leaves model 1's layers one slot out of place
+    rng = np.random.default_rng(5)
+    d0 = [_ints(rng, (1, 4)) for _ in layers]
+    d1 = [_ints(rng, (1, 4)) for _ in layers]
+    zero = [np.zeros((1, 4), np.float32) for _ in layers]
+    merged = oracle.merge(layers, [d0, d1], [0, 1])
+    got = oracle.retrieve(layers, merged, zero, 0, 1.0)
+    for t in range(5):
+        assert np.array_equal(got[t], d0[t] + d1[(t - 1) % 5])
 
 
 def test_integer_inputs_sum_exactly_in_any_order():
