@@ -197,6 +197,23 @@ int randes_delta_stats(const randes_layer *layers, int32_t n_layers,
                        const void *const *delta_b, uint64_t seed_b,
                        randes_dtype dtype, double *out3, void *hip_stream);
 
+/* randes_delta_stats for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same
+ * result, bit for bit, as randes_delta_stats; the call consists of kernel launches only (no
+ * hipMalloc, hipFree or hipMemcpy, nothing cached).  The descriptor tables of the call and its
+ * per-workgroup partial sums go to a fixed 8 MiB array inside the library's code object (one copy per
+ * GPU, held until the process ends) instead of allocated memory; the tables travel inside kernel
+ * arguments.  Limits: the tables must fit 1 MiB (a few thousand layers) and the partial sums 7 MiB
+ * (305834 workgroups: about 10^10 bf16 or 5 * 10^9 f32 elements per stack); beyond either the call
+ * returns RANDES_ENOTSUP and enqueues nothing.  Nothing in the array needs clearing between calls.
+ * Every call on a GPU uses that GPU's one array: calls on the same stream run in order and are safe;
+ * calls that overlap in time on different streams of one GPU race on it and must be ordered by the
+ * caller. */
+int randes_delta_stats_noalloc(const randes_layer *layers, int32_t n_layers,
+                               const void *const *delta_a, uint64_t seed_a,
+                               const void *const *delta_b, uint64_t seed_b,
+                               randes_dtype dtype, double *out3, void *hip_stream);
+
 /* LoRA front-end (Sec. "Parameter Efficient Finetuning (PEFT) Model Compression":
  * Theta_i = Theta_0 + lambda L_i): materialise the dense adapter update
  *   delta_out[r][c] = scale * sum_{t < rank} B[r][t] * A[t][c]

@@ -24,7 +24,8 @@ LIB_PATH = os.path.join(_HERE, "librandes.so")
 
 # include/randes.h: the method's calls
 EXPORTS = ["randes_layer_perm", "randes_source_table", "randes_sign_mask", "randes_merge", "randes_merge_weights",
-           "randes_retrieve", "randes_retrieve_many", "randes_update", "randes_delta_stats", "randes_lora_materialize",
+           "randes_retrieve", "randes_retrieve_many", "randes_update", "randes_delta_stats", "randes_delta_stats_noalloc",
+           "randes_lora_materialize",
            "randes_lora_materialize_batched", "randes_lora_merge", "randes_strerror", "randes_shutdown"]
 # include/randes_bench.h: measurement aids
 BENCH_EXPORTS = ["randes_set_tile_rows", "randes_set_tile_cols", "randes_set_fold", "randes_probe_stream"]
@@ -65,6 +66,7 @@ def lib():
                                        vp, ctypes.c_int, vp]
     L.randes_update.argtypes = [vp, i32, vp, ctypes.c_int, vp, ctypes.c_int, u64, i32, vp]
     L.randes_delta_stats.argtypes = [vp, i32, vp, u64, vp, u64, ctypes.c_int, vp, vp]
+    L.randes_delta_stats_noalloc.argtypes = [vp, i32, vp, u64, vp, u64, ctypes.c_int, vp, vp]
     L.randes_lora_materialize.argtypes = [vp, vp, i64, i64, i32, ctypes.c_float, ctypes.c_int, vp,
                                           ctypes.c_int, vp]
     L.randes_lora_materialize_batched.argtypes = [i32, vp, vp, vp, vp, i32, ctypes.c_float, ctypes.c_int,
@@ -288,16 +290,20 @@ def update(layers, merged, delta, seed, remove=False, stream=None):
     return merged
 
 
-def delta_stats(layers, delta_a, seed_a, delta_b, seed_b, out=None, stream=None):
-    """(<a',b'>, <a',a'>, <b',b'>) of two transformed deltas as a float64 GPU tensor of 3."""
+def delta_stats(layers, delta_a, seed_a, delta_b, seed_b, out=None, stream=None, noalloc=False):
+    """(<a',b'>, <a',a'>, <b',b'>) of two transformed deltas as a float64 GPU tensor of 3.
+    ``noalloc`` calls randes_delta_stats_noalloc (then ``out`` must be given: nothing is allocated)."""
     lt = _layer_table(layers)
     at, bt = _ptr_table(delta_a, lt), _ptr_table(delta_b, lt)
     if at.dtype != bt.dtype:
         raise TypeError("both deltas must share a dtype")
     if out is None:
+        if noalloc:
+            raise ValueError("the no-allocation call needs its output tensor")
         out = torch.empty(3, dtype=torch.float64, device=at.tensors[0].device)
-    _check(lib().randes_delta_stats(lt.array, lt.n, at.array, _u64(seed_a), bt.array, _u64(seed_b), at.code,
-                                    ctypes.c_void_p(out.data_ptr()), _stream(stream)))
+    fn = lib().randes_delta_stats_noalloc if noalloc else lib().randes_delta_stats
+    _check(fn(lt.array, lt.n, at.array, _u64(seed_a), bt.array, _u64(seed_b), at.code,
+              ctypes.c_void_p(out.data_ptr()), _stream(stream)))
     return out
 
 

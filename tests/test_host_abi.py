@@ -39,7 +39,8 @@ def test_the_method_header_holds_only_calls_that_cite_the_paper():
     for name in rb.BENCH_EXPORTS:
         assert name not in header
     for name in rb.EXPORTS:
-        if name in ("randes_strerror", "randes_shutdown", "randes_lora_materialize_batched", "randes_source_table"):
+        if name in ("randes_strerror", "randes_shutdown", "randes_lora_materialize_batched", "randes_source_table",
+                    "randes_delta_stats_noalloc"):     # the last one names the callers it is for instead
             continue
         decl = header.index("int %s(" % name)
         comment = header.rfind("/*", 0, decl)
