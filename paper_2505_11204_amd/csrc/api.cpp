@@ -155,7 +155,11 @@ struct CachedPlan {
     void *extra = nullptr;    // scratch inside the blob (stats partials)
     bool pinned = false;      // recorded into a HIP graph: its tables must outlive the cache's turnover
     StreamArgs vec{}, scl{};
-    size_t items_bytes = 0, segs_bytes = 0;   // LoRA launches: where the segment and coarse tables start
+    // LoRA launches: where the segment and workgroup tables start, and the launch shape chosen for them
+    size_t items_bytes = 0, segs_bytes = 0;
+    uint32_t lora_tiles = 0;
+    LoraShape lora_shape{};
+    bool lora_fast = false;
 };
 using PlanRef = std::shared_ptr<CachedPlan>;
 
@@ -329,6 +333,10 @@ struct Span { uintptr_t lo, hi; int tag; };
 // True if any span tagged 0 overlaps any span tagged 1.
 bool overlap(std::vector<Span> spans)
 {
+    // common case first, without sorting: everything tagged 0 lies entirely before or after everything tagged 1
+    uintptr_t lo[2] = { ~(uintptr_t)0, ~(uintptr_t)0 }, hi[2] = { 0, 0 };
+    for (const Span &s : spans) { lo[s.tag] = std::min(lo[s.tag], s.lo); hi[s.tag] = std::max(hi[s.tag], s.hi); }
+    if (hi[0] <= lo[1] || hi[1] <= lo[0]) return false;
     std::sort(spans.begin(), spans.end(), [](const Span &a, const Span &b) { return a.lo < b.lo; });
     uintptr_t hi0 = 0, hi1 = 0;   // furthest end seen so far per tag
     for (const Span &s : spans) {
@@ -341,7 +349,8 @@ bool overlap(std::vector<Span> spans)
 // True if any two of the spans overlap.
 bool any_overlap(std::vector<Span> spans)
 {
-    std::sort(spans.begin(), spans.end(), [](const Span &a, const Span &b) { return a.lo < b.lo; });
+    auto by_lo = [](const Span &a, const Span &b) { return a.lo < b.lo; };
+    if (!std::is_sorted(spans.begin(), spans.end(), by_lo)) std::sort(spans.begin(), spans.end(), by_lo);
     uintptr_t hi = 0;
     for (const Span &s : spans) {
         if (s.lo < hi) return true;
@@ -861,54 +870,56 @@ int randes_delta_stats(const randes_layer *layers, int32_t n_layers,
 
 namespace {
 
-// Upload (or find) the item and segment tables of a LoRA launch and enqueue it.
-int run_lora(std::vector<LoraItem> &items, const std::vector<LoraSeg> &segs, int32_t rank, float scale,
-             int ab_dtype, int out_dtype, void *hip_stream)
+// Tables of a LoRA launch: choose the band shape, cut the matrices into workgroup tiles, upload.
+int build_lora_tables(std::vector<LoraItem> &items, const std::vector<LoraSeg> &segs, int32_t rank, int ab_dtype,
+                      CachedPlan *fresh)
 {
     uint64_t tiles = 0;
     uint32_t max_seg = 1;
-    for (const LoraItem &it : items) max_seg = std::max(max_seg, it.n_seg);
-    const int64_t wg_rows = (int64_t)LORA_TILE_M * lora_row_tiles((int32_t)max_seg, rank);
+    bool fast = (rank % 8) == 0;
+    for (const LoraItem &it : items) {
+        max_seg = std::max(max_seg, it.n_seg);
+        fast = fast && (it.cols % 8) == 0 && aligned16(it.out);
+        // the wide path addresses with 32-bit byte offsets inside a matrix
+        fast = fast && (int64_t)it.rows * it.cols < ((int64_t)1 << 30) && (int64_t)it.rows * rank < ((int64_t)1 << 30) &&
+               (int64_t)it.cols * rank < ((int64_t)1 << 30);
+    }
+    for (const LoraSeg &sg : segs) fast = fast && aligned16(sg.A) && aligned16(sg.B);
+    const LoraShape shape = lora_choose_shape(items.data(), items.size(), (int32_t)max_seg, rank, ab_dtype == RANDES_F32);
+    const int64_t wg_rows = (int64_t)32 * shape.rt * shape.rb;
     for (LoraItem &it : items) {
-        it.tiles_x = (uint32_t)(((int64_t)it.cols + LORA_TILE_N - 1) / LORA_TILE_N);
+        it.tiles_x = (uint32_t)(((int64_t)it.cols + shape.tile_cols - 1) / shape.tile_cols);
         it.tile_begin = (uint32_t)tiles;
         tiles += (uint64_t)it.tiles_x * (uint64_t)(((int64_t)it.rows + wg_rows - 1) / wg_rows);
         if (tiles >= ((uint64_t)1 << 31)) return fail(RANDES_ENOTSUP, "too many tiles for one launch");
     }
     const size_t items_bytes = (sizeof(LoraItem) * items.size() + 255) & ~(size_t)255;
     const size_t segs_bytes = (sizeof(LoraSeg) * segs.size() + 255) & ~(size_t)255;
-    const int32_t head[3] = { 100, (int32_t)items.size(), (int32_t)segs.size() };
-    CallKey key;
-    key.add(head, sizeof(head));
-    key.add(items.data(), sizeof(LoraItem) * items.size());
-    key.add(segs.data(), sizeof(LoraSeg) * segs.size());
+    std::vector<char> host(items_bytes + segs_bytes + (size_t)tiles * sizeof(uint32_t), 0);
+    memcpy(host.data(), items.data(), sizeof(LoraItem) * items.size());
+    memcpy(host.data() + items_bytes, segs.data(), sizeof(LoraSeg) * segs.size());
+    uint32_t *wg_item = (uint32_t *)(host.data() + items_bytes + segs_bytes);
+    for (size_t q = 0; q < items.size(); ++q) {
+        const uint64_t end = q + 1 < items.size() ? items[q + 1].tile_begin : tiles;
+        for (uint64_t t = items[q].tile_begin; t < end; ++t) wg_item[t] = (uint32_t)q;
+    }
+    hipError_t e = hipMalloc(&fresh->blob, host.size());
+    if (e != hipSuccess) { fresh->blob = nullptr; return hip_fail(e, "hipMalloc(lora tables)"); }
+    e = hipMemcpy(fresh->blob, host.data(), host.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) { (void)hipFree(fresh->blob); fresh->blob = nullptr; return hip_fail(e, "hipMemcpy(lora tables)"); }
+    fresh->items_bytes = items_bytes;
+    fresh->segs_bytes = segs_bytes;
+    fresh->lora_tiles = (uint32_t)tiles;
+    fresh->lora_shape = shape;
+    fresh->lora_fast = fast;
+    return RANDES_OK;
+}
 
-    PlanRef cp;
-    int rc = find_or_build(key, hip_stream, &cp, [&](CachedPlan *fresh) -> int {
-        std::vector<uint32_t> coarse;
-        uint32_t item = 0;
-        const uint64_t n_chunks = (tiles + 63) / 64;
-        for (uint64_t i = 0; i <= n_chunks; ++i) {
-            const uint64_t tile = std::min<uint64_t>(i * 64, tiles - 1);
-            while (item + 1 < items.size() && items[item + 1].tile_begin <= tile) ++item;
-            coarse.push_back(item);
-        }
-        std::vector<char> host(items_bytes + segs_bytes + coarse.size() * sizeof(uint32_t), 0);
-        memcpy(host.data(), items.data(), sizeof(LoraItem) * items.size());
-        memcpy(host.data() + items_bytes, segs.data(), sizeof(LoraSeg) * segs.size());
-        memcpy(host.data() + items_bytes + segs_bytes, coarse.data(), coarse.size() * sizeof(uint32_t));
-        hipError_t e = hipMalloc(&fresh->blob, host.size());
-        if (e != hipSuccess) { fresh->blob = nullptr; return hip_fail(e, "hipMalloc(lora tables)"); }
-        e = hipMemcpy(fresh->blob, host.data(), host.size(), hipMemcpyHostToDevice);
-        if (e != hipSuccess) { (void)hipFree(fresh->blob); fresh->blob = nullptr; return hip_fail(e, "hipMemcpy(lora tables)"); }
-        return RANDES_OK;
-    });
-    if (rc) return rc;
-    hipError_t e = launch_lora((const LoraItem *)cp->blob, (int32_t)items.size(),
-                               (const LoraSeg *)((const char *)cp->blob + items_bytes),
-                               (const uint32_t *)((const char *)cp->blob + items_bytes + segs_bytes), (uint32_t)tiles,
-                               (int32_t)max_seg, rank, scale,
-                               ab_dtype, out_dtype, (hipStream_t)hip_stream);
+int launch_cached_lora(const CachedPlan &cp, int32_t rank, float scale, int ab_dtype, int out_dtype, void *hip_stream)
+{
+    hipError_t e = launch_lora((const LoraItem *)cp.blob, (const LoraSeg *)((const char *)cp.blob + cp.items_bytes),
+                               (const uint32_t *)((const char *)cp.blob + cp.items_bytes + cp.segs_bytes), cp.lora_tiles,
+                               cp.lora_shape, cp.lora_fast, rank, scale, ab_dtype, out_dtype, (hipStream_t)hip_stream);
     if (e != hipSuccess) return hip_fail(e, "lora launch");
     return RANDES_OK;
 }
@@ -926,32 +937,52 @@ int randes_lora_materialize_batched(int32_t n, const void *const *Bs, const void
     if (rank < 1) return fail(RANDES_EINVAL, "rank < 1");
     if (!dtype_ok(ab_dtype) || !dtype_ok(out_dtype)) return fail(RANDES_EINVAL, "unknown dtype");
     if (!std::isfinite(scale)) return fail(RANDES_EINVAL, "scale is not finite");
-    std::vector<LoraItem> items((size_t)n);
-    std::vector<LoraSeg> segs((size_t)n);
-    std::vector<Span> out_spans, both;
     for (int32_t q = 0; q < n; ++q) {
         if (!Bs[q] || !As[q] || !outs[q]) return fail(RANDES_EINVAL, "NULL matrix pointer");
         if (!elem_aligned(Bs[q], ab_dtype) || !elem_aligned(As[q], ab_dtype) || !elem_aligned(outs[q], out_dtype))
             return fail(RANDES_EINVAL, "misaligned matrix pointer");
         if (rows[q] < 1 || cols[q] < 1) return fail(RANDES_EINVAL, "rows < 1 or cols < 1");
         if (rows[q] >= (int64_t)1 << 31 || cols[q] >= (int64_t)1 << 31) return fail(RANDES_ENOTSUP, "rows or cols >= 2^31");
-        LoraItem &it = items[(size_t)q];
-        memset(&it, 0, sizeof(it));
-        it.out = outs[q];
-        it.rows = (int32_t)rows[q]; it.cols = (int32_t)cols[q];
-        it.seg_begin = (uint32_t)q; it.n_seg = 1;
-        LoraSeg &sg = segs[(size_t)q];
-        memset(&sg, 0, sizeof(sg));
-        sg.B = Bs[q]; sg.A = As[q];
-        out_spans.push_back(span_of(outs[q], (size_t)rows[q] * (size_t)cols[q], out_dtype, 0));
-        both.push_back(out_spans.back());
-        both.push_back(span_of(Bs[q], (size_t)rows[q] * (size_t)rank, ab_dtype, 1));
-        both.push_back(span_of(As[q], (size_t)rank * (size_t)cols[q], ab_dtype, 1));
     }
     // workgroups read factors while others write outputs: nothing written may be a factor or another output
-    if (any_overlap(out_spans)) return fail(RANDES_EINVAL, "output matrices overlap each other");
-    if (overlap(both)) return fail(RANDES_EINVAL, "an output matrix overlaps a factor");
-    return run_lora(items, segs, rank, scale, ab_dtype, out_dtype, hip_stream);
+    // (checked on every call: it needs no device, and a refused call must not depend on what is cached)
+    {
+        std::vector<Span> out_spans, both;
+        for (int32_t q = 0; q < n; ++q) {
+            out_spans.push_back(span_of(outs[q], (size_t)rows[q] * (size_t)cols[q], out_dtype, 0));
+            both.push_back(out_spans.back());
+            both.push_back(span_of(Bs[q], (size_t)rows[q] * (size_t)rank, ab_dtype, 1));
+            both.push_back(span_of(As[q], (size_t)rank * (size_t)cols[q], ab_dtype, 1));
+        }
+        if (any_overlap(out_spans)) return fail(RANDES_EINVAL, "output matrices overlap each other");
+        if (overlap(both)) return fail(RANDES_EINVAL, "an output matrix overlaps a factor");
+    }
+    const int32_t head[5] = { PLAN_LORA, n, rank, (int32_t)ab_dtype, (int32_t)out_dtype };
+    CallKey key;
+    key.add(head, sizeof(head));
+    key.add(Bs, sizeof(void *) * (size_t)n);
+    key.add(As, sizeof(void *) * (size_t)n);
+    key.add(rows, sizeof(int64_t) * (size_t)n);
+    key.add(cols, sizeof(int64_t) * (size_t)n);
+    key.add(outs, sizeof(void *) * (size_t)n);
+    PlanRef cp;
+    int rc = find_or_build(key, hip_stream, &cp, [&](CachedPlan *fresh) -> int {
+        std::vector<LoraItem> items((size_t)n);
+        std::vector<LoraSeg> segs((size_t)n);
+        for (int32_t q = 0; q < n; ++q) {
+            LoraItem &it = items[(size_t)q];
+            memset(&it, 0, sizeof(it));
+            it.out = outs[q];
+            it.rows = (int32_t)rows[q]; it.cols = (int32_t)cols[q];
+            it.seg_begin = (uint32_t)q; it.n_seg = 1;
+            LoraSeg &sg = segs[(size_t)q];
+            memset(&sg, 0, sizeof(sg));
+            sg.B = Bs[q]; sg.A = As[q];
+        }
+        return build_lora_tables(items, segs, rank, ab_dtype, fresh);
+    });
+    if (rc) return rc;
+    return launch_cached_lora(*cp, rank, scale, ab_dtype, out_dtype, hip_stream);
 }
 
 int randes_lora_merge(const randes_layer *layers, int32_t n_layers,
@@ -970,47 +1001,66 @@ int randes_lora_merge(const randes_layer *layers, int32_t n_layers,
     for (int64_t q = 0; q < (int64_t)n_tasks * n_layers; ++q)
         if (!Bs[q] || !As[q] || !elem_aligned(Bs[q], ab_dtype) || !elem_aligned(As[q], ab_dtype))
             return fail(RANDES_EINVAL, "NULL or misaligned factor pointer");
-    std::vector<Span> out_spans, both;
-    for (int32_t l = 0; l < n_layers; ++l) {
+    for (int32_t l = 0; l < n_layers; ++l)
         if (!merged[l] || !elem_aligned(merged[l], merged_dtype)) return fail(RANDES_EINVAL, "NULL or misaligned merged pointer");
-        const size_t rows = (size_t)layers[l].rows, cols = (size_t)layers[l].cols;
-        out_spans.push_back(span_of(merged[l], rows * cols, merged_dtype, 0));
-        both.push_back(out_spans.back());
-        for (int32_t i = 0; i < n_tasks; ++i) {
-            both.push_back(span_of(Bs[(size_t)i * n_layers + l], rows * (size_t)rank, ab_dtype, 1));
-            both.push_back(span_of(As[(size_t)i * n_layers + l], (size_t)rank * cols, ab_dtype, 1));
+    for (int32_t l = 0; l < n_layers; ++l)
+        if (layers[l].rows >= (int64_t)1 << 31) return fail(RANDES_ENOTSUP, "rows >= 2^31");
+    {
+        std::vector<Span> out_spans, both;
+        for (int32_t l = 0; l < n_layers; ++l) {
+            const size_t rows = (size_t)layers[l].rows, cols = (size_t)layers[l].cols;
+            out_spans.push_back(span_of(merged[l], rows * cols, merged_dtype, 0));
+            both.push_back(out_spans.back());
+            for (int32_t i = 0; i < n_tasks; ++i) {
+                both.push_back(span_of(Bs[(size_t)i * n_layers + l], rows * (size_t)rank, ab_dtype, 1));
+                both.push_back(span_of(As[(size_t)i * n_layers + l], (size_t)rank * cols, ab_dtype, 1));
+            }
         }
+        if (any_overlap(out_spans)) return fail(RANDES_EINVAL, "merged matrices overlap each other");
+        if (overlap(both)) return fail(RANDES_EINVAL, "a merged matrix overlaps a factor");
     }
-    if (any_overlap(out_spans)) return fail(RANDES_EINVAL, "merged matrices overlap each other");
-    if (overlap(both)) return fail(RANDES_EINVAL, "a merged matrix overlaps a factor");
-    std::vector<std::vector<int32_t>> src((size_t)n_tasks);
-    for (int32_t i = 0; i < n_tasks; ++i) {
-        rc = build_source_table(layers, n_layers, seeds[i], &src[(size_t)i], &why);
-        if (rc) return fail(rc, why);
-    }
-    std::vector<LoraItem> items((size_t)n_layers);
-    std::vector<LoraSeg> segs;
-    segs.reserve((size_t)n_layers * (size_t)n_tasks);
-    for (int32_t l = 0; l < n_layers; ++l) {
-        LoraItem &it = items[(size_t)l];
-        memset(&it, 0, sizeof(it));
-        it.out = merged[l];
-        it.rows = (int32_t)layers[l].rows; it.cols = (int32_t)layers[l].cols;
-        it.seg_begin = (uint32_t)segs.size(); it.n_seg = (uint32_t)n_tasks;
+    const int32_t head[6] = { PLAN_LORA_MERGE, n_layers, n_tasks, rank, (int32_t)ab_dtype, (int32_t)merged_dtype };
+    CallKey key;
+    key.add(head, sizeof(head));
+    key.add(layers, sizeof(randes_layer) * (size_t)n_layers);
+    key.add(Bs, sizeof(void *) * (size_t)n_tasks * (size_t)n_layers);
+    key.add(As, sizeof(void *) * (size_t)n_tasks * (size_t)n_layers);
+    key.add(seeds, sizeof(uint64_t) * (size_t)n_tasks);
+    key.add(merged, sizeof(void *) * (size_t)n_layers);
+    PlanRef cp;
+    rc = find_or_build(key, hip_stream, &cp, [&](CachedPlan *fresh) -> int {
+        std::string why2;
+        std::vector<std::vector<int32_t>> src((size_t)n_tasks);
         for (int32_t i = 0; i < n_tasks; ++i) {
-            LoraSeg sg;
-            memset(&sg, 0, sizeof(sg));
-            const int32_t t = src[(size_t)i][(size_t)l];
-            sg.B = Bs[(size_t)i * n_layers + t];
-            sg.A = As[(size_t)i * n_layers + t];
-            sg.key_lo = (uint32_t)(seeds[i] & 0xffffffffu);
-            sg.key_hi = (uint32_t)(seeds[i] >> 32);
-            sg.layer_id = (uint32_t)l;
-            sg.flip = (layers[l].flags & RANDES_FLIP) ? 1u : 0u;
-            segs.push_back(sg);
+            const int rc2 = build_source_table(layers, n_layers, seeds[i], &src[(size_t)i], &why2);
+            if (rc2) return fail(rc2, why2);
         }
-    }
-    return run_lora(items, segs, rank, scale, ab_dtype, merged_dtype, hip_stream);
+        std::vector<LoraItem> items((size_t)n_layers);
+        std::vector<LoraSeg> segs;
+        segs.reserve((size_t)n_layers * (size_t)n_tasks);
+        for (int32_t l = 0; l < n_layers; ++l) {
+            LoraItem &it = items[(size_t)l];
+            memset(&it, 0, sizeof(it));
+            it.out = merged[l];
+            it.rows = (int32_t)layers[l].rows; it.cols = (int32_t)layers[l].cols;
+            it.seg_begin = (uint32_t)segs.size(); it.n_seg = (uint32_t)n_tasks;
+            for (int32_t i = 0; i < n_tasks; ++i) {
+                LoraSeg sg;
+                memset(&sg, 0, sizeof(sg));
+                const int32_t t = src[(size_t)i][(size_t)l];
+                sg.B = Bs[(size_t)i * n_layers + t];
+                sg.A = As[(size_t)i * n_layers + t];
+                sg.key_lo = (uint32_t)(seeds[i] & 0xffffffffu);
+                sg.key_hi = (uint32_t)(seeds[i] >> 32);
+                sg.layer_id = (uint32_t)l;
+                sg.flip = (layers[l].flags & RANDES_FLIP) ? 1u : 0u;
+                segs.push_back(sg);
+            }
+        }
+        return build_lora_tables(items, segs, rank, ab_dtype, fresh);
+    });
+    if (rc) return rc;
+    return launch_cached_lora(*cp, rank, scale, ab_dtype, merged_dtype, hip_stream);
 }
 
 int randes_lora_materialize(const void *B, const void *A, int64_t rows, int64_t cols, int32_t rank,

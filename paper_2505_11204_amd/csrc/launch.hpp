@@ -38,11 +38,19 @@ struct LoraSeg {
     const void *A;        // rank x cols
     uint32_t key_lo, key_hi, layer_id, flip;   // the sign diagonal D (flip = 0: identity)
 };
-// coarse_dev[i] = matrix holding workgroup 64 * i, for i = 0 .. ceil(n_tiles / 64); max_seg = most
-// segments of any matrix (chooses the kernel variant).
-hipError_t launch_lora(const LoraItem *items_dev, int32_t n_items, const LoraSeg *segs_dev, const uint32_t *coarse_dev,
-                       uint32_t n_tiles, int32_t max_seg, int32_t rank, float scale, int dt_ab, int dt_out, hipStream_t s);
-// (the tile count must have been computed with lora_row_tiles(max_seg, rank) row blocks per workgroup)
+// Shape of a LoRA launch: nw waves side by side, nb blocks of 32 columns per wave (a workgroup's band
+// is tile_cols = nw * nb * 32 columns wide); a workgroup walks down rb groups of rt blocks of 32 rows
+// (32 * rt * rb rows per workgroup tile).
+struct LoraShape { int nw, nb, rt, rb, tile_cols; };
+// The band width that wastes the fewest columns over the launch's matrices; rt from the depth of the
+// deepest product (max_seg segments of `rank`); rb from the size of the launch.  Host code.
+LoraShape lora_choose_shape(const LoraItem *items, size_t n_items, int32_t max_seg, int32_t rank, bool f32_factors);
+// wg_item_dev[t] = matrix of workgroup tile t (tiles of a matrix: column band fastest, then row block;
+// tile_begin / tiles_x of the items computed for `shape`).  fast: every matrix has cols a multiple of 8,
+// rank a multiple of 8 and 16-byte aligned operands; otherwise operands and results move by element.
+hipError_t launch_lora(const LoraItem *items_dev, const LoraSeg *segs_dev, const uint32_t *wg_item_dev,
+                       uint32_t n_tiles, const LoraShape &shape, bool fast, int32_t rank, float scale,
+                       int dt_ab, int dt_out, hipStream_t s);
 
 // Columns per lane of the vector kernels for a call whose widest-count stream
 // holds bf16 (8) or only f32 (4).
@@ -77,16 +85,6 @@ inline int two_input_burst_rows(int dt_x, int dt_y, int vec)
 constexpr uint64_t PROBE_CHUNK_BYTES = 4u * 256u * 16u;
 hipError_t launch_probe(const void *const *inputs, int n_inputs, void *output, uint64_t bytes, int write, hipStream_t s);
 
-// Workgroup tile of the LoRA kernel.
-constexpr int LORA_TILE_M = 32, LORA_TILE_N = 512;
-constexpr int LORA_DEPTH_SLICE = 16;    // depth (segments x rank) handled per staged slab
-// Blocks of LORA_TILE_M rows one workgroup handles, one after the other, with the same staged
-// operand fragments: 4 when the product is one depth slice deep (measured best for plain
-// materialisation), 8 when it is deeper and staging costs more (superposed adapters, rank > 16).
-inline int lora_row_tiles(int32_t max_seg, int32_t rank)
-{
-    const int64_t slices = (int64_t)max_seg * ((rank + LORA_DEPTH_SLICE - 1) / LORA_DEPTH_SLICE);
-    return slices <= 1 ? 4 : 8;
-}
+constexpr int LORA_DEPTH_SLICE = 16;    // depth (segments x rank) values fetched and multiplied per step
 
 }  // namespace randes

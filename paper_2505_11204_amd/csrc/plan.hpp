@@ -64,7 +64,7 @@ struct HostPlan {
 };
 
 enum PlanKind { PLAN_MERGE = 1, PLAN_RETRIEVE = 2, PLAN_UPDATE = 3, PLAN_MERGE_WEIGHTS = 4, PLAN_STATS = 5,
-                PLAN_RETRIEVE_MANY = 6 };
+                PLAN_RETRIEVE_MANY = 6, PLAN_LORA = 7, PLAN_LORA_MERGE = 8 };
 
 int validate_layers(const randes_layer *layers, int32_t n_layers, std::string *why);
 
