@@ -213,3 +213,17 @@ def shadow_rows(rows, n_pick, seed):
     rnd = torch.randint(0, rows, (max(n_pick - len(fixed), 0),), generator=g).tolist()
     picks = sorted({r for r in fixed + rnd if 0 <= r < rows})
     return picks
+
+
+def tile_band_rows(rows, band=64, seed=99):
+    """Row indices for denser full-size parity: every row of the first ``band`` rows, of a band
+    in the middle (starting at a multiple of ``band``) and of the last ``band`` rows, plus the
+    scattered rows of :func:`shadow_rows`.  The streaming kernels cut a layer into tiles of at
+    most 32 rows that span a column range, so each band holds at least one whole row of tiles
+    from its first to its last column, with its neighbours' edges.  Depends on ``rows`` and
+    ``seed`` only, like :func:`shadow_rows`."""
+    mid = (rows // 2) // band * band
+    picks = set(shadow_rows(rows, 16, seed))
+    for start in (0, mid, rows - band):
+        picks.update(r for r in range(start, start + band) if 0 <= r < rows)
+    return sorted(picks)

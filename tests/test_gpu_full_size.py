@@ -1,8 +1,9 @@
 """GPU parity at the benchmark configurations' full sizes, in the launch
 configuration the benchmark times.  ViT-B/32-shaped: every element against the
 oracle.  The larger stacks are generated on the device; the oracle recomputes
-sampled rows of every layer (first/last rows, tile edges, random rows), which
-is exact because neither the sign masks nor the permutations depend on the row."""
+sampled rows of every layer (scattered rows, and for the 7B stack whole bands of
+consecutive rows that hold complete tiles), which is exact because neither the
+sign masks nor the permutations depend on the row."""
 import os
 
 import numpy as np
@@ -53,7 +54,11 @@ def test_vit_b32_every_element():
             _sampled_retrieve_check(stack, gm, gb, go, seeds[i], 1.0, "f32", "f32", "f32")
 
 
-def _row_sets(stack, n_pick=16):
+def _row_sets(stack, n_pick=16, bands=False):
+    """Sampled rows per layer: scattered rows, or (bands) whole bands of 64 consecutive rows at the
+    top, the middle and the bottom of every layer, which hold complete tiles of every kernel."""
+    if bands:
+        return [wl.tile_band_rows(l.rows) for l in stack]
     return [wl.shadow_rows(l.rows, n_pick, 99) for l in stack]
 
 
@@ -78,14 +83,15 @@ def _sampled_retrieve_check(stack, gm, gb, go, seed, lam, d_merged, d_base, d_ou
         _same_bits(got[l], want[l], "sampled retrieve layer %d" % l)
 
 
-def _sampled_stack_parity(stack, K, dtype, seeds, lam, retrieve_tasks, delta_std, scales=None, deltas=None, base=None):
+def _sampled_stack_parity(stack, K, dtype, seeds, lam, retrieve_tasks, delta_std, scales=None, deltas=None, base=None,
+                          bands=False):
     layers = layers_of(stack)
     if deltas is None:
         base, deltas = wl.make_inputs(stack, K, dtype=dtype, device="cuda", data_seed=1234,
                                       delta_std=delta_std, scales=scales)
     gm = rb.merge(layers, deltas, seeds)
     torch.cuda.synchronize()
-    rs = _row_sets(stack)
+    rs = _row_sets(stack, bands=bands)
     sh = _shadow(stack, rs)
     sh_deltas = [gather_rows(d, rs) for d in deltas]
     want_m = oracle.merge(sh, sh_deltas, seeds, CODE[dtype], CODE[dtype], n_threads=8)
@@ -135,9 +141,11 @@ def test_t5_base_lora_variant_sampled_rows():
     _sampled_stack_parity(stack, K, "bf16", [42 + i for i in range(K)], 1.0, [2], 1e-3, deltas=deltas, base=base)
 
 
-def test_llama_7b_bf16_sampled_rows():
+def test_llama_7b_bf16_whole_tile_bands():
+    # every layer: all rows of the first, a middle and the last 64-row band (complete tiles of both kernels
+    # over the full width) plus scattered rows
     K = 8
-    _sampled_stack_parity(wl.llama_7b(), K, "bf16", [42 + i for i in range(K)], 1.0, [0, 3, 7], 5e-4)
+    _sampled_stack_parity(wl.llama_7b(), K, "bf16", [42 + i for i in range(K)], 1.0, [0, 3, 7], 5e-4, bands=True)
 
 
 def _every_element_parity(stack, K, dtype, seeds, lam, retrieve_tasks, delta_std, scales=None):
@@ -209,7 +217,7 @@ def test_llama_7b_four_models_in_one_pass_sampled_rows():
             _same_bits(got[l], want[l], "request %d layer %d" % (q, l))
 
 
-def test_llama_7b_in_the_benchmark_layout_sampled_rows():
+def test_llama_7b_in_the_benchmark_layout_whole_tile_bands():
     # the stacks exactly where the benchmark puts them: one large allocation, cut by measured address
     # groups (merged and base in one group, the output stack across a group boundary)
     from paper_2505_11204_amd import placement
@@ -234,7 +242,7 @@ def test_llama_7b_in_the_benchmark_layout_sampled_rows():
     _, out = wl.alloc_stack(stack, td, "cuda", into=arena.flat(layout["out"], n, td))
     rb.merge(layers, deltas, seeds, merged=merged)
     torch.cuda.synchronize()
-    rs = _row_sets(stack)
+    rs = _row_sets(stack, bands=True)
     sh = _shadow(stack, rs)
     want_m = oracle.merge(sh, [gather_rows(d, rs) for d in deltas], seeds, CODE[dtype], CODE[dtype], n_threads=8)
     got_m = gather_rows(merged, rs)
