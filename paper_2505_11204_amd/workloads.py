@@ -215,11 +215,11 @@ def shadow_rows(rows, n_pick, seed):
     return picks
 
 
-def tile_band_rows(rows, band=64, seed=99):
+def tile_band_rows(rows, band=128, seed=99):
     """Row indices for denser full-size parity: every row of the first ``band`` rows, of a band
     in the middle (starting at a multiple of ``band``) and of the last ``band`` rows, plus the
     scattered rows of :func:`shadow_rows`.  The streaming kernels cut a layer into tiles of at
-    most 32 rows that span a column range, so each band holds at least one whole row of tiles
+    most 64 rows that span a column range, so each band holds at least one whole row of tiles
     from its first to its last column, with its neighbours' edges.  Depends on ``rows`` and
     ``seed`` only, like :func:`shadow_rows`."""
     mid = (rows // 2) // band * band

@@ -55,7 +55,7 @@ def test_vit_b32_every_element():
 
 
 def _row_sets(stack, n_pick=16, bands=False):
-    """Sampled rows per layer: scattered rows, or (bands) whole bands of 64 consecutive rows at the
+    """Sampled rows per layer: scattered rows, or (bands) whole bands of 128 consecutive rows at the
     top, the middle and the bottom of every layer, which hold complete tiles of every kernel."""
     if bands:
         return [wl.tile_band_rows(l.rows) for l in stack]
@@ -142,7 +142,7 @@ def test_t5_base_lora_variant_sampled_rows():
 
 
 def test_llama_7b_bf16_whole_tile_bands():
-    # every layer: all rows of the first, a middle and the last 64-row band (complete tiles of both kernels
+    # every layer: all rows of the first, a middle and the last 128-row band (complete tiles of both kernels
     # over the full width) plus scattered rows
     K = 8
     _sampled_stack_parity(wl.llama_7b(), K, "bf16", [42 + i for i in range(K)], 1.0, [0, 3, 7], 5e-4, bands=True)

@@ -176,12 +176,12 @@ def test_bad_arguments_are_error_codes_not_crashes(lib):
 
 
 def test_row_samplers_of_the_full_size_tests():
-    # the bands hold every row of three 64-row ranges (whole tiles of at most 32 rows) and the scattered rows;
+    # the bands hold every row of three 128-row ranges (whole tiles of at most 64 rows) and the scattered rows;
     # layers of one shape sample the same rows, whatever their place in the stack
     from paper_2505_11204_amd import workloads as wl
     rows = wl.tile_band_rows(11008)
-    for start in (0, 5504 // 64 * 64, 11008 - 64):
-        assert set(range(start, start + 64)) <= set(rows)
+    for start in (0, 5504 // 128 * 128, 11008 - 128):
+        assert set(range(start, start + 128)) <= set(rows)
     assert set(wl.shadow_rows(11008, 16, 99)) <= set(rows)
     assert rows == sorted(set(rows)) and rows[0] == 0 and rows[-1] == 11007
     assert wl.tile_band_rows(100) == list(range(100))
