@@ -38,6 +38,14 @@
  *  - Threads: every entry point may be called from several host threads at
  *    once; the cache is locked only while a table set is looked up or added,
  *    never across planning, uploads or launches.
+ *  - When the tables of an argument set are built (its first call), every
+ *    buffer is checked against the HIP runtime's records: it must be memory
+ *    HIP knows, not memory of another device than the current one, and its
+ *    allocation must hold all rows x cols elements of its layer; otherwise
+ *    RANDES_EINVAL, before anything is enqueued.  Cached calls skip the check
+ *    (freeing a buffer and calling again with its stale pointer is the
+ *    caller's error).  randes_sign_mask and randes_delta_stats_noalloc, which
+ *    build no cached tables, do not check.
  *  - Layer pointers must be aligned to their element size (else RANDES_EINVAL).
  *    16-byte aligned layers whose cols is a multiple of 4 (f32) / 8 (bf16)
  *    take the vectorised kernels; anything else takes a slower element-wise

@@ -364,6 +364,41 @@ Span span_of(const void *p, size_t elems, int dtype, int tag)
     return Span{ (uintptr_t)p, (uintptr_t)p + elems * elem_bytes(dtype), tag };
 }
 
+// Every buffer of a call must be memory that HIP knows, reachable from device `dev`, and must lie
+// inside its allocation for all the elements the kernels will touch: a kernel handed anything else
+// faults the GPU.  Runs when the tables of an argument set are built, not on cached calls; buffers
+// that share an allocation (views into one stack) cost one query.
+int spans_on_device(const std::vector<Span> &spans, int dev)
+{
+    uintptr_t known_lo = 0, known_hi = 0;   // allocation of the span checked last
+    for (const Span &s : spans) {
+        if (s.lo == s.hi || (s.lo >= known_lo && s.hi <= known_hi)) continue;
+        hipPointerAttribute_t at;
+        hipError_t e = hipPointerGetAttributes(&at, (const void *)s.lo);
+        if (e != hipSuccess || at.type == hipMemoryTypeUnregistered) {
+            (void)hipGetLastError();
+            return fail(RANDES_EINVAL, "a buffer pointer is not memory known to HIP (device memory expected)");
+        }
+        if (at.type == hipMemoryTypeDevice && at.device != dev)
+            return fail(RANDES_EINVAL, "a buffer lies on device " + std::to_string(at.device) +
+                                       ", the call was made with device " + std::to_string(dev) + " current");
+        void *base = nullptr;
+        size_t size = 0;
+        e = hipMemGetAddressRange((hipDeviceptr_t *)&base, &size, (hipDeviceptr_t)s.lo);
+        if (e != hipSuccess) {      // no range on record for this kind of memory: nothing to compare with
+            (void)hipGetLastError();
+            known_lo = known_hi = 0;
+            continue;
+        }
+        known_lo = (uintptr_t)base;
+        known_hi = known_lo + size;
+        if (s.hi > known_hi)
+            return fail(RANDES_EINVAL, "a buffer holds fewer elements than its layer's rows x cols: it ends " +
+                                       std::to_string(s.hi - known_hi) + " bytes past its allocation");
+    }
+    return RANDES_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -442,6 +477,7 @@ int merge_impl(const randes_layer *layers, int32_t n_layers,
             if (base) spans.push_back(span_of(base[l], n, delta_dtype, 1));
         }
         if (overlap(spans)) return fail(RANDES_EINVAL, "merged overlaps an input");
+        if (int bad = spans_on_device(spans, fresh->device)) return bad;
 
         HostPlan hp;
         std::string why2;
@@ -550,6 +586,9 @@ int randes_retrieve(const randes_layer *layers, int32_t n_layers,
         }
         if (overlap(a)) return fail(RANDES_EINVAL, "out overlaps merged");
         if (overlap(b)) return fail(RANDES_EINVAL, "out partially overlaps base");
+        for (int32_t l = 0; l < n_layers; ++l)
+            a.push_back(span_of(base[l], (size_t)layers[l].rows * (size_t)layers[l].cols, base_dtype, 1));
+        if (int bad = spans_on_device(a, fresh->device)) return bad;
 
         HostPlan hp;
         std::string why2;
@@ -609,6 +648,14 @@ int retrieve_many_pass(const randes_layer *layers, int32_t n_layers, const void 
 
     PlanRef cp;
     int rc = find_or_build(key, hip_stream, &cp, [&](CachedPlan *fresh) -> int {
+        std::vector<Span> spans;
+        for (int32_t l = 0; l < n_layers; ++l) {
+            const size_t n = (size_t)layers[l].rows * (size_t)layers[l].cols;
+            spans.push_back(span_of(merged[l], n, dtype, 1));
+            spans.push_back(span_of(base[l], n, dtype, 1));
+            for (int32_t i = 0; i < q; ++i) spans.push_back(span_of(outs[(size_t)i * n_layers + l], n, dtype, 0));
+        }
+        if (int bad = spans_on_device(spans, fresh->device)) return bad;
         HostPlan hp;
         std::string why;
         std::vector<std::vector<int32_t>> src((size_t)q);
@@ -733,6 +780,7 @@ int randes_update(const randes_layer *layers, int32_t n_layers,
             spans.push_back(span_of(delta[l], n, delta_dtype, 1));
         }
         if (overlap(spans)) return fail(RANDES_EINVAL, "merged overlaps delta");
+        if (int bad = spans_on_device(spans, fresh->device)) return bad;
         HostPlan hp;
         std::string why2;
         std::vector<int32_t> src;
@@ -842,6 +890,14 @@ int randes_delta_stats(const randes_layer *layers, int32_t n_layers,
 
     PlanRef cp;
     rc = find_or_build(key, hip_stream, &cp, [&](CachedPlan *fresh) -> int {
+        std::vector<Span> spans;
+        for (int32_t l = 0; l < n_layers; ++l) {
+            const size_t n = (size_t)layers[l].rows * (size_t)layers[l].cols;
+            spans.push_back(span_of(delta_a[l], n, dtype, 1));
+            spans.push_back(span_of(delta_b[l], n, dtype, 1));
+        }
+        spans.push_back(Span{ (uintptr_t)out3, (uintptr_t)out3 + 3 * sizeof(double), 0 });
+        if (int bad = spans_on_device(spans, fresh->device)) return bad;
         HostPlan hp;
         const int rc2 = build_stats_plan(layers, n_layers, delta_a, seed_a, delta_b, seed_b, dtype, &hp);
         if (rc2) return rc2;
@@ -946,8 +1002,9 @@ int randes_lora_materialize_batched(int32_t n, const void *const *Bs, const void
     }
     // workgroups read factors while others write outputs: nothing written may be a factor or another output
     // (checked on every call: it needs no device, and a refused call must not depend on what is cached)
+    std::vector<Span> both;
     {
-        std::vector<Span> out_spans, both;
+        std::vector<Span> out_spans;
         for (int32_t q = 0; q < n; ++q) {
             out_spans.push_back(span_of(outs[q], (size_t)rows[q] * (size_t)cols[q], out_dtype, 0));
             both.push_back(out_spans.back());
@@ -967,6 +1024,7 @@ int randes_lora_materialize_batched(int32_t n, const void *const *Bs, const void
     key.add(outs, sizeof(void *) * (size_t)n);
     PlanRef cp;
     int rc = find_or_build(key, hip_stream, &cp, [&](CachedPlan *fresh) -> int {
+        if (int bad = spans_on_device(both, fresh->device)) return bad;
         std::vector<LoraItem> items((size_t)n);
         std::vector<LoraSeg> segs((size_t)n);
         for (int32_t q = 0; q < n; ++q) {
@@ -1005,8 +1063,9 @@ int randes_lora_merge(const randes_layer *layers, int32_t n_layers,
         if (!merged[l] || !elem_aligned(merged[l], merged_dtype)) return fail(RANDES_EINVAL, "NULL or misaligned merged pointer");
     for (int32_t l = 0; l < n_layers; ++l)
         if (layers[l].rows >= (int64_t)1 << 31) return fail(RANDES_ENOTSUP, "rows >= 2^31");
+    std::vector<Span> both;
     {
-        std::vector<Span> out_spans, both;
+        std::vector<Span> out_spans;
         for (int32_t l = 0; l < n_layers; ++l) {
             const size_t rows = (size_t)layers[l].rows, cols = (size_t)layers[l].cols;
             out_spans.push_back(span_of(merged[l], rows * cols, merged_dtype, 0));
@@ -1029,6 +1088,7 @@ int randes_lora_merge(const randes_layer *layers, int32_t n_layers,
     key.add(merged, sizeof(void *) * (size_t)n_layers);
     PlanRef cp;
     rc = find_or_build(key, hip_stream, &cp, [&](CachedPlan *fresh) -> int {
+        if (int bad = spans_on_device(both, fresh->device)) return bad;
         std::string why2;
         std::vector<std::vector<int32_t>> src((size_t)n_tasks);
         for (int32_t i = 0; i < n_tasks; ++i) {

@@ -243,6 +243,45 @@ def test_empty_and_invalid_requests_are_rejected():
         rb.merge(layers, [], [])                               # no models
 
 
+def test_buffers_that_are_not_this_devices_memory_or_too_small_are_rejected():
+    # checked against the runtime's records when the tables of an argument set are built: nothing is launched
+    import ctypes
+    lib = rb.lib()
+    n_layers, K = 1, 2
+    good = [torch.zeros(8, 256, device="cuda") for _ in range(K + 3)]
+    layer = rb.LayerTable([(8, 256, -1, 1)])
+    seeds = (ctypes.c_uint64 * K)(1, 2)
+
+    def ptrs(*addresses):
+        return (ctypes.c_void_p * len(addresses))(*addresses)
+    host = np.zeros((8, 256), dtype=np.float32)       # ordinary host memory, unknown to HIP
+    d0, d1, m = good[0].data_ptr(), good[1].data_ptr(), good[2].data_ptr()
+    rc = lib.randes_merge(layer.array, n_layers, ptrs(d0, host.ctypes.data), K, seeds, 0, ptrs(m), 0, None)
+    assert rc == -1 and "not memory known to HIP" in lib.randes_strerror(rc).decode()
+    rc = lib.randes_retrieve(layer.array, n_layers, ptrs(m), 0, ptrs(host.ctypes.data), 0, ctypes.c_uint64(1),
+                             ctypes.c_float(1.0), ptrs(good[3].data_ptr()), 0, None)
+    assert rc == -1 and "not memory known to HIP" in lib.randes_strerror(rc).decode()
+    # a delta of 64 MiB behind a layer of 96 MiB (the merged buffer does hold 96 MiB); of three such deltas at
+    # least one lies where its claimed extent does not run into the merged buffer, which would be refused as overlap
+    mib = 1 << 20
+    torch.cuda.empty_cache()          # so that each tensor below is an allocation of its own size
+    big_m = torch.zeros(96 * mib // 4, device="cuda")
+    small = [torch.zeros(64 * mib // 4, device="cuda") for _ in range(3)]
+    free = [t for t in small if t.data_ptr() + 96 * mib <= big_m.data_ptr() or t.data_ptr() >= big_m.data_ptr() + 96 * mib]
+    assert free
+    big = rb.LayerTable([(96 * mib // 4 // 4096, 4096, -1, 1)])
+    one_seed = (ctypes.c_uint64 * 1)(7)
+    rc = lib.randes_merge(big.array, n_layers, ptrs(free[0].data_ptr()), 1, one_seed, 0, ptrs(big_m.data_ptr()), 0, None)
+    assert rc == -1 and "past its allocation" in lib.randes_strerror(rc).decode()
+    torch.cuda.synchronize()
+    assert float(big_m.abs().sum()) == 0.0
+    torch.cuda.synchronize()
+    assert all(float(t.abs().sum()) == 0.0 for t in good)     # nothing was written
+    # the same pointers with their true shape are accepted
+    assert lib.randes_merge(layer.array, n_layers, ptrs(d0, d1), K, seeds, 0, ptrs(m), 0, None) == 0
+    torch.cuda.synchronize()
+
+
 # ------------------------------------------------------------------ hot swap
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 def test_hot_swap(dt):
