@@ -941,7 +941,7 @@ int build_lora_tables(std::vector<LoraItem> &items, const std::vector<LoraSeg> &
                (int64_t)it.cols * rank < ((int64_t)1 << 30);
     }
     for (const LoraSeg &sg : segs) fast = fast && aligned16(sg.A) && aligned16(sg.B);
-    const LoraShape shape = lora_choose_shape(items.data(), items.size(), (int32_t)max_seg, rank, ab_dtype == RANDES_F32);
+    const LoraShape shape = lora_choose_shape(items.data(), items.size(), (int32_t)max_seg, rank, ab_dtype == RANDES_F32, fast);
     const int64_t wg_rows = (int64_t)32 * shape.rt * shape.rb;
     for (LoraItem &it : items) {
         it.tiles_x = (uint32_t)(((int64_t)it.cols + shape.tile_cols - 1) / shape.tile_cols);

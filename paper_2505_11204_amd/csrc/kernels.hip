@@ -59,17 +59,6 @@ __device__ __forceinline__ void widen(const uint32_t (&raw)[NumWords<DT, VEC>::v
     }
 }
 
-// Sign bits of columns [col, col + VEC) of one (model, slot layer): bit j set
-// means D is -1 at column col + j.  col is a multiple of VEC and VEC divides 32.
-template <int VEC>
-__device__ __forceinline__ uint32_t lane_sign_bits(uint32_t key_lo, uint32_t key_hi, uint32_t layer, uint32_t col)
-{
-    const u32x4_t o = sign_block(key_lo, key_hi, layer, col >> 7);
-    const uint32_t sel = (col >> 5) & 3u;
-    const uint32_t word = sel == 0 ? o.w[0] : sel == 1 ? o.w[1] : sel == 2 ? o.w[2] : o.w[3];
-    return (word >> (col & 31u)) & ((VEC == 32) ? 0xffffffffu : ((1u << VEC) - 1u));
-}
-
 // One register per task: this lane's sign bits arranged so that a shift and an AND give the XOR
 // mask of any raw dword.  f32: bit j is element j.  bf16 pairs: the even elements' bits sit at
 // 12..15 and the odd elements' at 28..31, so dword j uses (W << (3 - j)) & 0x80008000.
@@ -639,13 +628,26 @@ __global__ void __launch_bounds__(WG) stats_finalize_kernel(const double *partia
     if (threadIdx.x < 3) out3[threadIdx.x] = sh[0][threadIdx.x];
 }
 
-// One byte per column: 1 where D is -1.
+// One byte per column: 1 where D is -1.  The bits take the road they take in the streaming kernels:
+// the workgroup stages the generator blocks of its "tile" in LDS and every lane picks its bit out of
+// them.  Tiles are 192 columns wide, so every other one starts in the middle of a 128-column block.
+constexpr uint32_t MASK_TILE_COLS = 192;
 __global__ void __launch_bounds__(WG) sign_mask_kernel(uint32_t key_lo, uint32_t key_hi, uint32_t layer,
                                                        int64_t cols, uint8_t *mask_out)
 {
-    const int64_t c = (int64_t)blockIdx.x * WG + threadIdx.x;
-    if (c >= cols) return;
-    mask_out[c] = (uint8_t)lane_sign_bits<1>(key_lo, key_hi, layer, (uint32_t)c);
+    __shared__ uint32_t sbits[3 * 4];   // at most 3 blocks cover 192 columns
+    Tile t{};
+    t.L.flip = 1u;
+    t.L.layer_id = layer;
+    t.L.sign_blocks = 0u;
+    t.tile_col0 = blockIdx.x * MASK_TILE_COLS;
+    t.cw = MASK_TILE_COLS;
+    t.col_in_tile = threadIdx.x;
+    const uint32_t nblk = stage_sign_bits(sbits, t, nullptr, 1u, key_lo, key_hi);
+    __syncthreads();
+    const int64_t c = (int64_t)t.tile_col0 + threadIdx.x;
+    if (threadIdx.x >= MASK_TILE_COLS || c >= cols) return;
+    mask_out[c] = (uint8_t)lane_bits_from_lds<1>(sbits, t, nblk, 0u);
 }
 
 // ---------------------------------------------------------------------------
@@ -899,7 +901,7 @@ hipError_t launch_stats_finalize(const double *partials, uint32_t n_partials, do
 hipError_t launch_sign_mask(uint32_t key_lo, uint32_t key_hi, uint32_t layer, int64_t cols,
                             uint8_t *mask_out, hipStream_t s)
 {
-    const uint32_t blocks = (uint32_t)((cols + WG - 1) / WG);
+    const uint32_t blocks = (uint32_t)((cols + MASK_TILE_COLS - 1) / MASK_TILE_COLS);
     hipLaunchKernelGGL(sign_mask_kernel, dim3(blocks), dim3(WG), 0, s, key_lo, key_hi, layer, cols, mask_out);
     return hipGetLastError();
 }

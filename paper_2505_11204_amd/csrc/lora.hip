@@ -26,14 +26,24 @@
 // of the two blocks interleave into 8 adjacent output columns.  The sign flip is an XOR on the
 // loaded dwords; the workgroup produces the sign bits of its band once, one lane per (model, 128
 // columns), and keeps them in LDS.  Slices of 16 depth values are fetched a few slices ahead of the
-// one being multiplied, through a ring of register buffers.  Deep products (superposed adapters) are
-// bound by fetching and issuing rather than by the write: they run in small workgroups (four waves),
-// of which several fit a CU, with two row blocks sharing every fetch of A.
+// one being multiplied, through a ring of register buffers.  Deep products (high ranks) are bound by
+// fetching and issuing rather than by the write: they run in small workgroups (four waves), of which
+// several fit a CU, with two row blocks sharing every fetch of A.
+//
+// Superpositions of up to 8 depth slices (8 adapters of rank 16, 4 of rank 32, ...) go one step
+// further: a wave's 64 columns do not change while its workgroup walks down the band, so the wave
+// fetches, flips and regroups its fragments of A for all slices once and keeps them in registers
+// (64 of them); a row block then costs 16 bytes per lane and slice of B, requested one block ahead,
+// 16 MFMAs and the store.  Such a workgroup walks far (the launch is cut so that the chip is filled
+// about once), which pays for the one fetch of A: 8 adapters on 72 matrices of 768 x 768 in 23 us
+// against 45 us the streaming way.
 //
 // Operand layout of the 32x32 MFMAs: lane L supplies row (L % 32) of the left operand and column
 // (L % 32) of the right operand for the depth slice owned by lane half (L / 32); accumulator
 // register v of lane L is row 8*(v/4) + 4*(L/32) + (v%4), column L % 32 of the product.
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 
 #include "device_util.hpp"
 #include "launch.hpp"
@@ -59,6 +69,8 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 constexpr int KCH = LORA_DEPTH_SLICE;   // depth values per slice (one 32x32x16 MFMA, or eight 32x32x2)
 constexpr int LORA_SIGN_SEGS = 32;      // segments whose sign bits a workgroup keeps in LDS
 constexpr int LORA_RT2_SLICES = 4;     // depth slices from which two row blocks share every fetch of A
+constexpr int LORA_RES_SLICES = 8;     // deepest product whose fragments of A stay in registers
+constexpr double LORA_RES_FIXED = 5.0; // what such a workgroup spends before its first row block, in row blocks
 
 struct LoraArgs {
     const LoraItem *items;
@@ -344,10 +356,15 @@ template <int DTO, int TN> struct StageBytes {
 // PF steps (a step = one depth slice of one group) are fetched ahead of the one being multiplied.
 // FAST: every matrix of the launch has cols a multiple of 8, rank a multiple of 8 and operands
 // aligned for the wide accesses (checked on the host); otherwise operands and results move by element.
-template <int DTAB, int DTO, int NW, int NB, int RT, int PF, bool FAST>
+// RES > 0: products of at most RES depth slices (superposed adapters, ranks of 64 to 128) keep the
+// flipped, regrouped fragments of A of all their slices in registers: a wave's columns do not change
+// while the workgroup walks down its band, so A is fetched once per workgroup instead of once per row
+// group, and a row block costs the 16 bytes per lane and slice of B, the multiplies and the store.
+template <int DTAB, int DTO, int NW, int NB, int RT, int PF, bool FAST, int RES = 0>
 __global__ void __launch_bounds__(NW * 64) lora_kernel(const LoraArgs P)
 {
     static_assert(NB % 2 == 0 && NB * 32 <= 128, "a wave's columns are whole 64-column spans inside one generator block");
+    static_assert(RES == 0 || (DTAB == DT_BF16 && FAST && RT == 1 && NB == 2), "resident fragments: bf16 factors, wide accesses, one row block, one span");
     constexpr int NT = NW * 64, TN = NW * NB * 32, NSPAN = NB / 2;
     constexpr int PITCH = StagePitch<DTO, TN>::value;
     // two images take turns: a wave may fill the next one while others still store the previous one,
@@ -393,11 +410,25 @@ __global__ void __launch_bounds__(NW * 64) lora_kernel(const LoraArgs P)
     // A lane holds output row l32 of each row block and, in the accumulator pair (E, O) of span sp,
     // the columns wave*NB*32 + sp*64 + 16*g + 8*half + (0..7) of the band for g = 0..3: register
     // 4*g + i of E is column +2*i, of O column +2*i + 1.
-    auto store_group = [&](int32_t grow0) {
+    // The registers a store takes its address and data from are not free for anything else until the
+    // store has completed.  Where stores and the next fetch alternate closely (RES), the pieces on
+    // their way out keep registers of their own, which are written again only when the next row
+    // block's pieces are ready, a whole row block later.
+    constexpr int NPIN = RES > 0 ? 2 * NB : 1;
+    u32x4 outq[1][NPIN];
+    uint32_t outo[1][NPIN];
+    if constexpr (RES > 0) {
+#pragma unroll
+        for (int h = 0; h < 1; ++h)
+#pragma unroll
+            for (int j = 0; j < NPIN; ++j) { outq[h][j] = u32x4{0u, 0u, 0u, 0u}; outo[h][j] = 0u; }
+    }
+    auto store_group = [&](int32_t grow0, auto set_tag) {
+        constexpr int SET = decltype(set_tag)::value;
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
             const int32_t brow0 = grow0 + rt * 32;
-            if (brow0 >= w.rows) break;   // uniform
+            if ((RES == 0 || rt > 0) && brow0 >= w.rows) break;   // uniform (a group's first block always exists)
             if constexpr (DTO == DT_BF16) {
                 char *stage = stage2[image % NIMG];
                 ++image;
@@ -422,7 +453,19 @@ __global__ void __launch_bounds__(NW * 64) lora_kernel(const LoraArgs P)
                     const int piece = j * NT + (int)tid;
                     const int r = piece / CPR, c8 = (piece % CPR) * 8;
                     const int32_t gr = brow0 + r, gc = col0 + c8;
-                    if (gr < w.rows && gc < w.cols) {
+                    if constexpr (RES > 0) asm volatile("" : "+v"(outq[SET][j]), "+v"(outo[SET][j]));   // this set's last pieces lived until here
+                    const bool inside = gr < w.rows && gc < w.cols;
+                    if constexpr (RES > 0) {
+                        // Every lane stores, whatever its piece: a store under a condition cannot be counted
+                        // when the code is compiled, and every later wait for a fetched operand would then
+                        // wait for the stores as well.  A lane whose piece lies outside the matrix stores the
+                        // band's first piece, which always lies inside, once more: the same bytes to the same place.
+                        const int rr = inside ? r : 0, cc = inside ? c8 : 0;
+                        outq[SET][j] = *(const u32x4 *)(stage + rr * PITCH + cc * 2);
+                        outo[SET][j] = ((uint32_t)(brow0 + rr) * (uint32_t)w.cols + (uint32_t)(col0 + cc)) * 2u;
+                        asm volatile("" : "+v"(outq[SET][j]), "+v"(outo[SET][j]));
+                        __builtin_nontemporal_store(outq[SET][j], (RANDES_GLOBAL u32x4 *)((gptr)it.out + outo[SET][j]));
+                    } else if (inside) {
                         const u32x4 q = *(const u32x4 *)(stage + r * PITCH + c8 * 2);
                         if constexpr (FAST) {   // cols a multiple of 8 and out 16-byte aligned
                             __builtin_nontemporal_store(q, (RANDES_GLOBAL u32x4 *)((gptr)it.out + ((uint32_t)gr * (uint32_t)w.cols + (uint32_t)gc) * 2u));
@@ -525,6 +568,101 @@ __global__ void __launch_bounds__(NW * 64) lora_kernel(const LoraArgs P)
     LoraOffsets<NSPAN, RT> off;
     int32_t off_grp = -1;
     if constexpr (FAST) lora_column_offsets<DTAB, NSPAN, RT>(w, off);
+    if constexpr (RES > 0) {
+        // The host sends here only launches whose every product has at most RES slices, rank a multiple
+        // of 16 (no slice runs past its segment) and at most LORA_SIGN_SEGS segments.
+        const int32_t n_sl = n_seg * slices_per_seg;
+        auto slice_seg = [&](int s) {   // slices beyond the product repeat its last one and are not multiplied
+            const int32_t sc = s < n_sl ? s : n_sl - 1;
+            return sc / slices_per_seg;
+        };
+        auto slice_k0 = [&](int s) {
+            const int32_t sc = s < n_sl ? s : n_sl - 1;
+            return (sc % slices_per_seg) * KCH;
+        };
+        // Lane sl of every wave looks up the operand pointers of slice sl once; afterwards a slice's base
+        // is two lane reads away (table look-ups inside the walk would put a chain of scalar loads and
+        // waits in front of every row block).
+        uint32_t a_lo, a_hi, b_lo, b_hi;
+        {
+            const int32_t my = (int32_t)(lane < (uint32_t)RES ? lane : 0u);
+            const int32_t sg = slice_seg(my), k0 = slice_k0(my);
+            const LoraSeg *gs = P.segs + it.seg_begin + sg;
+            const uint64_t ap = (uint64_t)gs->A + (uint64_t)((uint32_t)k0 * (uint32_t)w.cols * 2u);
+            const uint64_t bp = (uint64_t)gs->B + (uint64_t)((uint32_t)k0 * 2u);
+            a_lo = (uint32_t)ap; a_hi = (uint32_t)(ap >> 32);
+            b_lo = (uint32_t)bp; b_hi = (uint32_t)(bp >> 32);
+        }
+        auto lane_ptr = [](uint32_t lo, uint32_t hi, int sl) {
+            // the lane read returns a signed word: through unsigned, or the low half's top bit would
+            // smear over the high half
+            const uint32_t l = (uint32_t)__builtin_amdgcn_readlane((int)lo, sl), h = (uint32_t)__builtin_amdgcn_readlane((int)hi, sl);
+            return (gcptr)(((uint64_t)h << 32) | (uint64_t)l);
+        };
+        uint32_t araw[RES][8];
+#pragma unroll
+        for (int sl = 0; sl < RES; ++sl) {
+            const gcptr abase = lane_ptr(a_lo, a_hi, sl);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) araw[sl][j] = *(const RANDES_GLOBAL uint32_t *)(abase + off.a[0][j]);
+        }
+        // B of one row block: 16 bytes per lane and slice, rows clamped like everywhere on this path
+        auto fetch_b = [&](int32_t grp, u32x4 (&dst)[RES]) {
+            const int32_t g = grp < n_groups ? grp : n_groups - 1;
+            const int32_t row = (group0 + g) * 32 + (int32_t)w.l32;
+            const uint32_t rc = (uint32_t)(row < w.rows ? row : w.rows - 1);
+            const uint32_t boff = (rc * (uint32_t)w.rank + 8u * w.half) * 2u;
+#pragma unroll
+            for (int sl = 0; sl < RES; ++sl) dst[sl] = *(const RANDES_GLOBAL u32x4 *)(lane_ptr(b_lo, b_hi, sl) + boff);
+        };
+        u32x4 bb[2][RES];
+        fetch_b(0, bb[0]);
+        // flip and regroup A once: fragments of the even and of the odd column of this lane's pair
+        u32x4 fe[RES], fo[RES];
+#pragma unroll
+        for (int sl = 0; sl < RES; ++sl) {
+            const int32_t sg = uni(slice_seg(sl));
+            const uint32_t rel = (uint32_t)wband + 2u * w.l32;
+            const uint32_t bits = (ssign[(sg * NBLK + (int32_t)(rel >> 7)) * 4 + (int32_t)((rel >> 5) & 3u)] >> (rel & 31u)) & 3u;
+            const uint32_t m = ((bits & 1u) << 15) | ((bits & 2u) << 30);
+            uint32_t e[4], o[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t d0 = araw[sl][2 * j] ^ m, d1 = araw[sl][2 * j + 1] ^ m;
+                e[j] = __builtin_amdgcn_perm(d1, d0, 0x05040100u);
+                o[j] = __builtin_amdgcn_perm(d1, d0, 0x07060302u);
+            }
+            fe[sl].x = e[0]; fe[sl].y = e[1]; fe[sl].z = e[2]; fe[sl].w = e[3];
+            fo[sl].x = o[0]; fo[sl].y = o[1]; fo[sl].z = o[2]; fo[sl].w = o[3];
+        }
+        auto block = [&](int32_t grp, const u32x4 (&b)[RES], auto set_tag) {
+#pragma unroll
+            for (int sl = 0; sl < RES; ++sl) {
+                if (sl < n_sl) {   // uniform
+                    const bf16x8 bv = __builtin_bit_cast(bf16x8, b[sl]);
+                    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fe[sl]), bv, acc[0][0], 0, 0, 0);
+                    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fo[sl]), bv, acc[0][1], 0, 0, 0);
+                }
+            }
+            store_group((group0 + grp) * 32, set_tag);
+            clear();
+        };
+        // The B of the next row block is requested before this one is multiplied and stored.  The first
+        // block stands outside the loop, so that the loop is entered in the state every pass leaves
+        // behind (one block's operands requested, the block before it on its way out): the waits inside
+        // are compiled for what is really in flight, and no pass waits for the stores it follows.
+        fetch_b(1, bb[1]);
+        block(0, bb[0], std::integral_constant<int, 0>{});
+        for (int32_t g = 1; g < n_groups; g += 2) {
+            fetch_b(g + 1, bb[0]);
+            block(g, bb[1], std::integral_constant<int, 0>{});
+            if (g + 1 < n_groups) {   // uniform
+                fetch_b(g + 2, bb[1]);
+                block(g + 1, bb[0], std::integral_constant<int, 0>{});
+            }
+        }
+        return;
+    }
     auto fetch = [&](const Cursor &c, SliceRaw<DTAB, NSPAN, RT> &raw) {
         const int32_t grp = uni(c.grp);
         LoraLane wl = w;
@@ -550,7 +688,7 @@ __global__ void __launch_bounds__(NW * 64) lora_kernel(const LoraArgs P)
         }
         lora_multiply<DTAB, NSPAN, RT, FAST>(raw, bits, ks * KCH, wl, acc);
         if (ks == slices_per_seg - 1 && sg == n_seg - 1) {   // the group is complete
-            store_group(wl.row0);
+            store_group(wl.row0, std::integral_constant<int, 0>{});
             clear();
         }
     };
@@ -587,13 +725,18 @@ __global__ void __launch_bounds__(NW * 64) lora_kernel(const LoraArgs P)
 // take the widest band that wastes no columns, whole rows where it can.  Deeper ones (superposed
 // adapters, high ranks) spend their time fetching and multiplying and take small workgroups, of
 // which more fit a CU, with two row blocks side by side, which halves the fetches of A.
-LoraShape lora_choose_shape(const LoraItem *items, size_t n_items, int32_t max_seg, int32_t rank, bool f32_factors)
+LoraShape lora_choose_shape(const LoraItem *items, size_t n_items, int32_t max_seg, int32_t rank, bool f32_factors, bool fast)
 {
     static const int cand[3] = { 12, 8, 4 };
     const int64_t slices = (int64_t)max_seg * ((rank + KCH - 1) / KCH);
     LoraShape best{};
     best.nb = 2;
-    best.rt = (slices >= LORA_RT2_SLICES && !f32_factors) ? 2 : 1;
+    // Resident fragments for superpositions (measured: a single adapter of rank 64, whose one A stays
+    // in the caches anyway, is 3-6 % faster the streaming way; products of one or two slices, bound by
+    // the write, are 10 % faster in full-row bands).
+    best.res = (fast && !f32_factors && rank % KCH == 0 && max_seg >= 2 && slices >= LORA_RT2_SLICES &&
+                slices <= LORA_RES_SLICES && max_seg <= LORA_SIGN_SEGS) ? 1 : 0;
+    best.rt = (slices >= LORA_RT2_SLICES && !f32_factors && !best.res) ? 2 : 1;
     double best_waste = -1.0;
     for (const int nw : cand) {
         if (slices >= 4 && nw != 4) continue;
@@ -614,6 +757,22 @@ LoraShape lora_choose_shape(const LoraItem *items, size_t n_items, int32_t max_s
                   (((int64_t)items[q].rows + 32 * best.rt - 1) / (32 * best.rt));
     const int64_t rb = groups / (256 * 12);
     best.rb = (int)(rb < 1 ? 1 : (rb > 8 ? 8 : rb));
+    if (best.res) {
+        // Resident fragments pay the fetch of A once per workgroup: long walks, as long as the launch
+        // still fills the chip's places for such workgroups about once.
+        int best_rb = 1;
+        double best_cost = -1.0;
+        for (int cand_rb = 1; cand_rb <= 32; ++cand_rb) {
+            int64_t wgs = 0;
+            for (size_t q = 0; q < n_items; ++q)
+                wgs += (((int64_t)items[q].cols + best.tile_cols - 1) / best.tile_cols) *
+                       ((((int64_t)items[q].rows + 31) / 32 + cand_rb - 1) / cand_rb);
+            const double rounds = (double)((wgs + 511) / 512);   // the chip holds 512 such workgroups at once, two per CU
+            const double cost = rounds * (LORA_RES_FIXED + (double)cand_rb);   // in units of one row block
+            if (best_cost < 0.0 || cost < best_cost) { best_cost = cost; best_rb = cand_rb; }
+        }
+        best.rb = best_rb;
+    }
     return best;
 }
 
@@ -633,6 +792,16 @@ template <int DTAB, int DTO>
 static hipError_t lora_dispatch(const LoraArgs &a, const LoraShape &sh, bool fast, hipStream_t s)
 {
     if (sh.nb != 2) return hipErrorInvalidValue;
+    if (sh.res) {
+        if constexpr (DTAB == DT_BF16) {
+            if (sh.nw != 4 || sh.rt != 1 || !fast) return hipErrorInvalidValue;
+            const dim3 grid((a.n_tiles + 7u) / 8u * 8u), block(4 * 64);
+            hipLaunchKernelGGL((lora_kernel<DT_BF16, DTO, 4, 2, 1, LORA_PF, true, LORA_RES_SLICES>), grid, block, 0, s, a);
+            return hipGetLastError();
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
     const int sel = sh.nw * 10 + sh.rt;
     switch (sel) {
     case 121: lora_launch_one<DTAB, DTO, 12, 1>(a, fast, s); break;

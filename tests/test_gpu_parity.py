@@ -424,6 +424,31 @@ def test_fused_lora_merge(dt_ab, dt_out, rank, n_tasks):
             assert ((a - b).abs() <= bound).all()
 
 
+@pytest.mark.parametrize("dt_out", ["bf16", "f32"])
+@pytest.mark.parametrize("rank,n_tasks", [(16, 8), (16, 4), (16, 5), (16, 7), (32, 2), (32, 4), (64, 2), (16, 9)])
+def test_fused_lora_merge_of_superpositions_with_wide_accesses(dt_out, rank, n_tasks):
+    # Every matrix fit for 16-byte accesses (cols a multiple of 8, bf16 factors): products of 4 to 8 depth
+    # slices take the kernel that keeps all fragments of A in registers while it walks down its band (long
+    # walks of odd and even length, ragged last row blocks, bands wider than the matrix, slices short of 8),
+    # (16, 9) with its 9 slices the streaming kernel with two row blocks per fetch.
+    stack = [Layer(70, 520, 0, SRSF), Layer(1000, 264, 1, SRSF), Layer(70, 520, 0, SRSF), Layer(33, 8, -1, FLIP),
+             Layer(1000, 264, 1, SRSF), Layer(1, 1032, -1, FLIP), Layer(2049, 256, -1, FLIP), Layer(70, 520, 0, SRSF)]
+    layers = layers_of(stack)
+    seeds = [1000 + 7 * i for i in range(n_tasks)]
+    factors = wl.make_lora_factors(stack, list(range(len(stack))), n_tasks, rank=rank, dtype="bf16", device="cpu")
+    got = rb.lora_merge(layers, [[(B.cuda(), A.cuda()) for (B, A) in per] for per in factors], seeds, 0.75,
+                        merged_dtype=TD[dt_out])
+    want, mag = oracle.lora_merge(layers, [[(to_np(B), to_np(A)) for (B, A) in per] for per in factors], seeds, 0.75,
+                                  CODE["bf16"])
+    for l in range(len(stack)):
+        g = got[l].float().cpu().numpy().astype(np.float64)
+        tol = n_tasks * rank * 2.0 ** -24 * mag[l] + 2.0 ** -23 * np.abs(want[l]) + 1e-45
+        if dt_out == "bf16":
+            tol = tol + 2.0 ** -8 * np.abs(want[l]) + 2.0 ** -133
+        err = np.abs(g - want[l])
+        assert (err <= tol).all(), (l, err.max())
+
+
 @pytest.mark.parametrize("dt,dt_merged", [("f32", "f32"), ("bf16", "bf16"), ("bf16", "f32")])
 @pytest.mark.parametrize("n_tasks", [1, 3, 4, 8, 11])
 def test_merge_from_weights(dt, dt_merged, n_tasks):
