@@ -41,7 +41,7 @@ struct LoraSeg {
 // Shape of a LoRA launch: nw waves side by side, nb blocks of 32 columns per wave (a workgroup's band
 // is tile_cols = nw * nb * 32 columns wide); a workgroup walks down rb groups of rt blocks of 32 rows
 // (32 * rt * rb rows per workgroup tile).
-struct LoraShape { int nw, nb, rt, rb, tile_cols, res; };   // res: fragments of A resident (deep products)
+struct LoraShape { int nw, nb, rt, rb, tile_cols, res; };   // res: depth slices whose fragments of A stay in registers (0: streamed)
 // The band width that wastes the fewest columns over the launch's matrices; rt from the depth of the
 // deepest product (max_seg segments of `rank`); rb from the size of the launch.  Host code.
 LoraShape lora_choose_shape(const LoraItem *items, size_t n_items, int32_t max_seg, int32_t rank, bool f32_factors, bool fast);

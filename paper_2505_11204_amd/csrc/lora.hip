@@ -36,7 +36,9 @@
 // (64 of them); a row block then costs 16 bytes per lane and slice of B, requested one block ahead,
 // 16 MFMAs and the store.  Such a workgroup walks far (the launch is cut so that the chip is filled
 // about once), which pays for the one fetch of A: 8 adapters on 72 matrices of 768 x 768 in 23 us
-// against 45 us the streaming way.
+// against 45 us the streaming way.  Products of one or two slices take the same simple walk in the
+// full-row bands (a few row blocks per workgroup): its waits are compiled exactly, where the ring's
+// loop drains the wave's memory queue once per turn, which is worth 3-7 %.
 //
 // Operand layout of the 32x32 MFMAs: lane L supplies row (L % 32) of the left operand and column
 // (L % 32) of the right operand for the depth slice owned by lane half (L / 32); accumulator
@@ -731,15 +733,20 @@ LoraShape lora_choose_shape(const LoraItem *items, size_t n_items, int32_t max_s
     const int64_t slices = (int64_t)max_seg * ((rank + KCH - 1) / KCH);
     LoraShape best{};
     best.nb = 2;
-    // Resident fragments for superpositions (measured: a single adapter of rank 64, whose one A stays
-    // in the caches anyway, is 3-6 % faster the streaming way; products of one or two slices, bound by
-    // the write, are 10 % faster in full-row bands).
-    best.res = (fast && !f32_factors && rank % KCH == 0 && max_seg >= 2 && slices >= LORA_RT2_SLICES &&
-                slices <= LORA_RES_SLICES && max_seg <= LORA_SIGN_SEGS) ? 1 : 0;
+    // Resident fragments: for superpositions of up to 8 slices (res = 8, 256-column bands, long walks),
+    // and for products of one or two slices, which are bound by the write (res = 2: the band shape and
+    // the short walks of the streaming kernel, 3-7 % faster than it).  A single adapter of rank 64, whose
+    // one A stays in the caches anyway, measured 3-6 % faster the streaming way and keeps it.
+    best.res = 0;
+    if (fast && !f32_factors && rank % KCH == 0 && max_seg <= LORA_SIGN_SEGS) {
+        if (slices <= 2) best.res = 2;
+        else if (max_seg >= 2 && slices <= LORA_RES_SLICES) best.res = LORA_RES_SLICES;
+    }
     best.rt = (slices >= LORA_RT2_SLICES && !f32_factors && !best.res) ? 2 : 1;
+    const bool deep = slices >= 4 || best.res == LORA_RES_SLICES;
     double best_waste = -1.0;
     for (const int nw : cand) {
-        if (slices >= 4 && nw != 4) continue;
+        if (deep && nw != 4) continue;
         const int64_t tn = (int64_t)nw * 64;
         double waste = 0.0;
         for (size_t q = 0; q < n_items; ++q) {
@@ -757,7 +764,8 @@ LoraShape lora_choose_shape(const LoraItem *items, size_t n_items, int32_t max_s
                   (((int64_t)items[q].rows + 32 * best.rt - 1) / (32 * best.rt));
     const int64_t rb = groups / (256 * 12);
     best.rb = (int)(rb < 1 ? 1 : (rb > 8 ? 8 : rb));
-    if (best.res) {
+    if (best.res == 2 && best.rb > 4) best.rb = 4;   // measured: walks of 3 or 4 row blocks
+    if (best.res == LORA_RES_SLICES) {
         // Resident fragments pay the fetch of A once per workgroup: long walks, as long as the launch
         // still fills the chip's places for such workgroups about once.
         int best_rb = 1;
@@ -794,9 +802,17 @@ static hipError_t lora_dispatch(const LoraArgs &a, const LoraShape &sh, bool fas
     if (sh.nb != 2) return hipErrorInvalidValue;
     if (sh.res) {
         if constexpr (DTAB == DT_BF16) {
-            if (sh.nw != 4 || sh.rt != 1 || !fast) return hipErrorInvalidValue;
-            const dim3 grid((a.n_tiles + 7u) / 8u * 8u), block(4 * 64);
-            hipLaunchKernelGGL((lora_kernel<DT_BF16, DTO, 4, 2, 1, LORA_PF, true, LORA_RES_SLICES>), grid, block, 0, s, a);
+            if (sh.rt != 1 || !fast) return hipErrorInvalidValue;
+            const dim3 grid((a.n_tiles + 7u) / 8u * 8u), block(sh.nw * 64);
+            if (sh.res == LORA_RES_SLICES && sh.nw == 4)
+                hipLaunchKernelGGL((lora_kernel<DT_BF16, DTO, 4, 2, 1, LORA_PF, true, LORA_RES_SLICES>), grid, block, 0, s, a);
+            else if (sh.res == 2 && sh.nw == 12)
+                hipLaunchKernelGGL((lora_kernel<DT_BF16, DTO, 12, 2, 1, LORA_PF, true, 2>), grid, block, 0, s, a);
+            else if (sh.res == 2 && sh.nw == 8)
+                hipLaunchKernelGGL((lora_kernel<DT_BF16, DTO, 8, 2, 1, LORA_PF, true, 2>), grid, block, 0, s, a);
+            else if (sh.res == 2 && sh.nw == 4)
+                hipLaunchKernelGGL((lora_kernel<DT_BF16, DTO, 4, 2, 1, LORA_PF, true, 2>), grid, block, 0, s, a);
+            else return hipErrorInvalidValue;
             return hipGetLastError();
         } else {
             return hipErrorInvalidValue;
