@@ -427,7 +427,7 @@ def ceilings(flats, merged_flat, out_flat):
 def timed_calls(fn, reps=10, burst=20):
     """(median ms of one call bracketed by its own pair of HIP events, which includes the latency of
     a launch into an idle queue; ms per call of `burst` calls issued back to back between one pair,
-    which is what the kernels themselves take)."""
+    which is what the kernels themselves take; microseconds the host spends issuing one such call)."""
     fn(); fn()
     torch.cuda.synchronize()
     ts = []
@@ -435,15 +435,17 @@ def timed_calls(fn, reps=10, burst=20):
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record(); fn(); b.record(); b.synchronize()
         ts.append(a.elapsed_time(b))
-    bs = []
+    bs, hs = [], []
     for _ in range(3):
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
+        t0 = time.perf_counter()
         for _ in range(burst):
             fn()
+        hs.append((time.perf_counter() - t0) / burst * 1e6)
         b.record(); b.synchronize()
         bs.append(a.elapsed_time(b) / burst)
-    return sorted(ts)[len(ts) // 2], sorted(bs)[1]
+    return sorted(ts)[len(ts) // 2], sorted(bs)[1], sorted(hs)[1]
 
 
 def lora_variant():
@@ -479,8 +481,8 @@ def lora_variant():
     rows = {}
 
     def row(name, nbytes, fn, with_flop=False):
-        ms_call, ms_burst = timed_calls(fn)
-        rows[name] = {"ms_per_call_alone": ms_call, "ms_back_to_back": ms_burst, "bytes": nbytes,
+        ms_call, ms_burst, host_us = timed_calls(fn)
+        rows[name] = {"ms_per_call_alone": ms_call, "ms_back_to_back": ms_burst, "host_us_per_call": host_us, "bytes": nbytes,
                       "GBs": nbytes / (ms_burst * 1e-3) / 1e9,
                       "frac_of_hbm_peak": nbytes / (ms_burst * 1e-3) / 1e9 / HBM_PEAK_GBS}
         if with_flop:

@@ -227,11 +227,27 @@ int current_device(int *dev)
 // into a graph is replayed with kernel arguments that point into its tables, so those are kept
 // until randes_shutdown(); the first call with an argument set allocates and copies synchronously
 // and is therefore refused while its stream is being captured.
+template <class Build, class Precheck>
+int find_or_build(const CallKey &k, void *hip_stream, PlanRef *out, Build build, Precheck precheck);
 template <class Build>
 int find_or_build(const CallKey &k, void *hip_stream, PlanRef *out, Build build)
 {
+    return find_or_build(k, hip_stream, out, build, []() { return (int)RANDES_OK; });
+}
+
+// `precheck` holds argument checks that are too costly for every call and whose verdict is the same
+// for equal arguments (overlap sweeps): it runs when the argument set is not cached, before
+// anything else, and also when no device can be asked, so that a bad argument is reported as such
+// on any machine.
+template <class Build, class Precheck>
+int find_or_build(const CallKey &k, void *hip_stream, PlanRef *out, Build build, Precheck precheck)
+{
     int dev, rc;
-    if ((rc = current_device(&dev))) return rc;
+    if ((rc = current_device(&dev))) {
+        const std::string no_device = randes_strerror(rc);
+        if (int bad = precheck()) return bad;
+        return fail(rc, no_device);
+    }
     const uint64_t h = k.hash();
     const bool capturing = stream_is_capturing(hip_stream);
     {
@@ -248,6 +264,7 @@ int find_or_build(const CallKey &k, void *hip_stream, PlanRef *out, Build build)
             return RANDES_OK;
         }
     }
+    if (int bad = precheck()) return bad;
     if (capturing)
         return fail(RANDES_ENOTSUP, "the first call with an argument set uploads its tables and cannot be recorded: "
                                     "call once eagerly before capturing the stream");
@@ -1001,9 +1018,9 @@ int randes_lora_materialize_batched(int32_t n, const void *const *Bs, const void
         if (rows[q] >= (int64_t)1 << 31 || cols[q] >= (int64_t)1 << 31) return fail(RANDES_ENOTSUP, "rows or cols >= 2^31");
     }
     // workgroups read factors while others write outputs: nothing written may be a factor or another output
-    // (checked on every call: it needs no device, and a refused call must not depend on what is cached)
+    // (swept when the argument set is first seen; equal arguments give an equal verdict)
     std::vector<Span> both;
-    {
+    auto no_overlap = [&]() -> int {
         std::vector<Span> out_spans;
         for (int32_t q = 0; q < n; ++q) {
             out_spans.push_back(span_of(outs[q], (size_t)rows[q] * (size_t)cols[q], out_dtype, 0));
@@ -1013,7 +1030,8 @@ int randes_lora_materialize_batched(int32_t n, const void *const *Bs, const void
         }
         if (any_overlap(out_spans)) return fail(RANDES_EINVAL, "output matrices overlap each other");
         if (overlap(both)) return fail(RANDES_EINVAL, "an output matrix overlaps a factor");
-    }
+        return RANDES_OK;
+    };
     const int32_t head[5] = { PLAN_LORA, n, rank, (int32_t)ab_dtype, (int32_t)out_dtype };
     CallKey key;
     key.add(head, sizeof(head));
@@ -1038,7 +1056,7 @@ int randes_lora_materialize_batched(int32_t n, const void *const *Bs, const void
             sg.B = Bs[q]; sg.A = As[q];
         }
         return build_lora_tables(items, segs, rank, ab_dtype, fresh);
-    });
+    }, no_overlap);
     if (rc) return rc;
     return launch_cached_lora(*cp, rank, scale, ab_dtype, out_dtype, hip_stream);
 }
@@ -1064,7 +1082,7 @@ int randes_lora_merge(const randes_layer *layers, int32_t n_layers,
     for (int32_t l = 0; l < n_layers; ++l)
         if (layers[l].rows >= (int64_t)1 << 31) return fail(RANDES_ENOTSUP, "rows >= 2^31");
     std::vector<Span> both;
-    {
+    auto no_overlap = [&]() -> int {   // swept when the argument set is first seen
         std::vector<Span> out_spans;
         for (int32_t l = 0; l < n_layers; ++l) {
             const size_t rows = (size_t)layers[l].rows, cols = (size_t)layers[l].cols;
@@ -1077,7 +1095,8 @@ int randes_lora_merge(const randes_layer *layers, int32_t n_layers,
         }
         if (any_overlap(out_spans)) return fail(RANDES_EINVAL, "merged matrices overlap each other");
         if (overlap(both)) return fail(RANDES_EINVAL, "a merged matrix overlaps a factor");
-    }
+        return RANDES_OK;
+    };
     const int32_t head[6] = { PLAN_LORA_MERGE, n_layers, n_tasks, rank, (int32_t)ab_dtype, (int32_t)merged_dtype };
     CallKey key;
     key.add(head, sizeof(head));
@@ -1118,7 +1137,7 @@ int randes_lora_merge(const randes_layer *layers, int32_t n_layers,
             }
         }
         return build_lora_tables(items, segs, rank, ab_dtype, fresh);
-    });
+    }, no_overlap);
     if (rc) return rc;
     return launch_cached_lora(*cp, rank, scale, ab_dtype, merged_dtype, hip_stream);
 }
