@@ -37,8 +37,9 @@ int randes_set_fold(int32_t enable);
  * device streams of `bytes` bytes each (16-byte aligned, bytes a multiple of 16384)
  * and, if write != 0, stores their element-wise 32-bit integer sum to output
  * (bytes bytes); if write == 0 nothing is stored and output only needs 16 valid
- * bytes.  Its bandwidth is the machine's practical ceiling for that mix of reads
- * and writes, reported beside the method's kernels by the benchmark. */
+ * bytes.  Its bandwidth is a point of comparison for that mix of reads and writes
+ * (one plain kernel of one launch shape, not an upper bound), reported beside the
+ * method's kernels by the benchmark. */
 int randes_probe_stream(const void *const *inputs, int32_t n_inputs, void *output, int64_t bytes, int32_t write,
                         void *hip_stream);
 

@@ -29,6 +29,9 @@ EXPORTS = ["randes_layer_perm", "randes_source_table", "randes_sign_mask", "rand
            "randes_lora_materialize_batched", "randes_lora_merge", "randes_strerror", "randes_shutdown"]
 # include/randes_bench.h: measurement aids
 BENCH_EXPORTS = ["randes_set_tile_rows", "randes_set_tile_cols", "randes_set_fold", "randes_probe_stream"]
+# include/randes_place.h: where stacks lie in device memory
+PLACE_EXPORTS = ["randes_place_classify", "randes_place_classify_device", "randes_place_serving_layout"]
+COPY_RATE_FN = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p)
 
 
 class RandesError(RuntimeError):
@@ -79,7 +82,10 @@ def lib():
     L.randes_set_tile_cols.argtypes = [i32]
     L.randes_set_fold.argtypes = [i32]
     L.randes_probe_stream.argtypes = [vp, i32, vp, i64, i32, vp]
-    for name in EXPORTS + BENCH_EXPORTS:
+    L.randes_place_classify.argtypes = [i32, COPY_RATE_FN, vp, ctypes.c_double, i32, vp]
+    L.randes_place_classify_device.argtypes = [vp, u64, i32, vp, vp]
+    L.randes_place_serving_layout.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp]
+    for name in EXPORTS + BENCH_EXPORTS + PLACE_EXPORTS:
         if name != "randes_strerror":
             getattr(L, name).restype = ctypes.c_int
     _lib = L

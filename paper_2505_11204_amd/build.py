@@ -11,9 +11,10 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librandes.so")
-SOURCES = ["kernels.hip", "lora.hip", "noalloc.hip", "plan.cpp", "api.cpp"]
+SOURCES = ["kernels.hip", "lora.hip", "noalloc.hip", "plan.cpp", "api.cpp", "place.cpp"]
 HEADERS = ["launch.hpp", "plan.hpp", "philox.hpp", "device_util.hpp", "api_internal.hpp",
-           os.path.join("..", "..", "include", "randes.h"), os.path.join("..", "..", "include", "randes_bench.h")]
+           os.path.join("..", "..", "include", "randes.h"), os.path.join("..", "..", "include", "randes_bench.h"),
+           os.path.join("..", "..", "include", "randes_place.h")]
 
 # -ffp-contract=off: the merge is adds only and the retrieve asks for its one fused
 # multiply-add explicitly, so nothing may be contracted behind the source's back.

@@ -10,12 +10,15 @@ the method follow suit:
   and the output stack is spread half and half over two other groups;
 * merge is fastest when the merged stack shares its group with none of the deltas.
 
-Nothing in the runtime reports the groups, so :func:`classify_chunks` finds them by
-timing plain copies between chunks of one large allocation, and
-:func:`plan_serving_layout` packs the stacks accordingly.  Both are pure functions of
-their inputs; :class:`Arena` supplies the device memory and the timing.  Placement is
-a property of the caller's allocations: the kernels take any pointers.
+Nothing in the runtime reports the groups, so the library finds them by timing plain
+copies between chunks of one large allocation and packs the stacks accordingly
+(``include/randes_place.h``); this module is the binding of those calls
+(:func:`classify_chunks`, :func:`plan_serving_layout`, both pure functions of their
+inputs) plus :class:`Arena`, which supplies the device memory.  Placement is a
+property of the caller's allocations: the kernels take any pointers.
 """
+import ctypes
+
 import torch
 
 from . import binding as rb
@@ -23,32 +26,8 @@ from . import binding as rb
 GIB = 1 << 30
 
 
-def _two_medians(values):
-    """Centres of a two-cluster split of a list of numbers (medians, so that a few
-    outliers do not become a cluster of their own), or None if one cluster is empty."""
-    vals = sorted(values)
-    lo, hi = vals[len(vals) // 10], vals[-1 - len(vals) // 10]
-    for _ in range(8):
-        mid = 0.5 * (lo + hi)
-        a = [v for v in vals if v < mid]
-        b = [v for v in vals if v >= mid]
-        if not a or not b:
-            return None
-        lo, hi = a[len(a) // 2], b[len(b) // 2]
-    return lo, hi
-
-
-def _middle_of_longest_run(chunks):
-    best, cur = [], []
-    for c in chunks:
-        cur = cur + [c] if cur and c == cur[-1] + 1 else [c]
-        if len(cur) > len(best):
-            best = cur
-    return best[len(best) // 2]
-
-
 def classify_chunks(n_chunks, rate, min_separation=0.02, max_groups=4):
-    """Label every chunk 0..n_chunks-1 with a group number.
+    """Label every chunk 0..n_chunks-1 with a group number (``randes_place_classify``).
 
     ``rate(r, w)`` is the measured rate of a copy that reads chunk r and writes chunk w.
     Chunks that copy slowly from a reference chunk are in its group, the others are
@@ -56,31 +35,20 @@ def classify_chunks(n_chunks, rate, min_separation=0.02, max_groups=4):
     into two clusters at least ``min_separation`` (relative) apart.  Groups come in long
     runs, so a majority vote over five neighbouring chunks removes single misreads.
     """
-    label = [-1] * n_chunks
-    rest, g = list(range(n_chunks)), 0
-    while len(rest) > 1 and g < max_groups - 1:
-        ref = _middle_of_longest_run(rest)
-        rates = {c: rate(ref, c) for c in rest if c != ref}
-        centres = _two_medians(list(rates.values()))
-        if centres is None or (centres[1] - centres[0]) / centres[1] < min_separation:
-            break
-        mid = 0.5 * (centres[0] + centres[1])
-        other = {c: (1 if v >= mid else 0) for c, v in rates.items()}
-        other[ref] = 0
-        voted = {}
-        for c in rest:
-            near = [other[x] for x in range(c - 2, c + 3) if x in other]
-            voted[c] = 1 if 2 * sum(near) > len(near) else 0
-        if min(sum(voted.values()), len(rest) - sum(voted.values())) < 3:
-            break                                # not a group, a handful of misreads
-        for c in rest:
-            if voted[c] == 0:
-                label[c] = g
-        rest = [c for c in rest if voted[c] == 1]
-        g += 1
-    for c in rest:
-        label[c] = g
-    return label
+    labels = (ctypes.c_int32 * n_chunks)()
+    failure = []
+
+    def call(r, w, _ctx):
+        try:
+            return float(rate(r, w))
+        except Exception as e:          # an exception must not unwind through the C caller
+            failure.append(e)
+            return 0.0
+    rb._check(rb.lib().randes_place_classify(n_chunks, rb.COPY_RATE_FN(call), None, float(min_separation),
+                                             int(max_groups), labels))
+    if failure:
+        raise failure[0]
+    return list(labels)
 
 
 def runs_of(labels):
@@ -93,12 +61,9 @@ def runs_of(labels):
     return out
 
 
-def _align_up(x, a=256):
-    return (x + a - 1) // a * a
-
-
 def plan_serving_layout(labels, chunk_bytes, stack_bytes, n_models, n_more_outputs=0):
-    """Byte offsets of the stacks of one serving set-up inside the classified allocation.
+    """Byte offsets of the stacks of one serving set-up inside the classified allocation
+    (``randes_place_serving_layout``).
 
     Returns ``{"merged", "base", "out", "deltas": [...], "more_outputs": [...], "read_group", "write_groups"}`` or
     None when the groups found do not allow the layout: the output stack lies across a
@@ -108,53 +73,18 @@ def plan_serving_layout(labels, chunk_bytes, stack_bytes, n_models, n_more_outpu
     Every stack is contiguous and stays one chunk away from the other group boundaries,
     whose position is only known to one chunk.
     """
-    rs = runs_of(labels)
-    if len(set(labels)) < 3:
-        return None
-    half = _align_up(stack_bytes // 2)
     n = len(labels)
-
-    def free_ranges(skip_boundary, out_span):
-        """(group, lo, hi) byte ranges usable for whole stacks."""
-        fr = []
-        for i, (g, a, b) in enumerate(rs):
-            lo = a * chunk_bytes + (chunk_bytes if a > 0 else 0)
-            hi = b * chunk_bytes - (chunk_bytes if b < n else 0)
-            if i == skip_boundary:          # run on the left of the straddled boundary
-                hi = min(b * chunk_bytes, out_span[0])
-            if i == skip_boundary + 1:      # run on its right
-                lo = max(a * chunk_bytes, out_span[1])
-            if hi > lo:
-                fr.append([g, _align_up(lo), hi])
-        return fr
-
-    def take(fr, ok_group):
-        for r in fr:
-            if ok_group(r[0]) and r[1] + stack_bytes <= r[2]:
-                off = r[1]
-                r[1] = _align_up(off + stack_bytes)
-                return off
+    lab = (ctypes.c_int32 * n)(*labels)
+    offs = (ctypes.c_uint64 * (3 + n_models + n_more_outputs))()
+    groups = (ctypes.c_int32 * 3)()
+    rc = rb.lib().randes_place_serving_layout(lab, n, int(chunk_bytes), int(stack_bytes), int(n_models),
+                                              int(n_more_outputs), offs, groups)
+    if rc == -2:        # RANDES_ENOTSUP: no such layout in these groups
         return None
-
-    for i in range(len(rs) - 1):
-        (g1, a1, b1), (g2, a2, b2) = rs[i], rs[i + 1]
-        edge = b1 * chunk_bytes
-        # half a stack and a chunk of margin on both sides of the boundary
-        if (b1 - a1) * chunk_bytes < half + chunk_bytes or (b2 - a2) * chunk_bytes < half + chunk_bytes:
-            continue
-        out_off = edge - half
-        out_span = (out_off, out_off + _align_up(stack_bytes))
-        for read_group in sorted(set(labels) - {g1, g2}):
-            fr = free_ranges(i, out_span)
-            merged = take(fr, lambda g: g == read_group)
-            base = take(fr, lambda g: g == read_group)
-            deltas = [take(fr, lambda g: g != read_group) for _ in range(n_models)]
-            more = [take(fr, lambda g: g != read_group) for _ in range(n_more_outputs)]
-            if merged is None or base is None or any(d is None for d in deltas + more):
-                continue
-            return {"merged": merged, "base": base, "out": out_off, "deltas": deltas, "more_outputs": more,
-                    "read_group": read_group, "write_groups": (g1, g2)}
-    return None
+    rb._check(rc)
+    offs = list(offs)
+    return {"merged": offs[0], "base": offs[1], "out": offs[2], "deltas": offs[3:3 + n_models],
+            "more_outputs": offs[3 + n_models:], "read_group": groups[0], "write_groups": (groups[1], groups[2])}
 
 
 class Arena:
@@ -191,7 +121,11 @@ class Arena:
         return 2.0 * self.chunk_bytes / best
 
     def classify(self):
-        return classify_chunks(self.n_chunks, self.copy_rate)
+        """Group of every chunk, from copies timed inside the library (``randes_place_classify_device``)."""
+        labels = (ctypes.c_int32 * self.n_chunks)()
+        rb._check(rb.lib().randes_place_classify_device(self.buf.data_ptr(), self.chunk_bytes, self.n_chunks,
+                                                        rb._stream(None), labels))
+        return list(labels)
 
     def flat(self, byte_offset, n_elements, dtype):
         """A 1-D tensor of ``dtype`` over the arena's bytes from ``byte_offset`` (256-aligned)."""

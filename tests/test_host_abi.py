@@ -22,7 +22,8 @@ def lib():
     return rb.lib()
 
 
-@pytest.mark.parametrize("header_name,exports", [("randes.h", rb.EXPORTS), ("randes_bench.h", rb.BENCH_EXPORTS)])
+@pytest.mark.parametrize("header_name,exports", [("randes.h", rb.EXPORTS), ("randes_bench.h", rb.BENCH_EXPORTS),
+                                                 ("randes_place.h", rb.PLACE_EXPORTS)])
 def test_library_exports_every_declared_symbol(lib, header_name, exports):
     header = open(os.path.join(ROOT, "include", header_name)).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)

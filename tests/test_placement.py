@@ -1,11 +1,13 @@
-"""Host logic of the HBM placement: finding address groups from copy rates and packing
-the stacks of a serving set-up into them.  The rates here come from a model of the
-behaviour measured on the device (same group slow, different groups fast, a little
-noise, a rare slow misread); no GPU is involved."""
+"""Host logic of the HBM placement (include/randes_place.h through its binding): finding
+address groups from copy rates and packing the stacks of a serving set-up into them.  The
+rates here come from a model of the behaviour measured on the device (same group slow,
+different groups fast, a little noise, a rare slow misread); no GPU is involved.  A second
+implementation in plain Python (tests/placement_reference.py) must agree on random cases."""
 import random
 
 import pytest
 
+import placement_reference as ref
 from paper_2505_11204_amd import placement as pl
 
 GIB = 1 << 30
@@ -110,3 +112,46 @@ def test_layout_needs_room():
     labels = [0] * 20 + [1] * 20 + [2] * 20          # 60 GiB cannot hold eleven 12.55 GiB stacks
     assert pl.plan_serving_layout(labels, GIB, STACK, 8) is None
     assert pl.plan_serving_layout([0] * 96 + [1] * 96, GIB, STACK, 8) is None     # two groups only
+
+
+def random_groups(rnd, n_chunks):
+    """A random map of 1 to 4 groups in runs of 8 chunks and more."""
+    n_groups = rnd.randint(1, 4)
+    out = []
+    while len(out) < n_chunks:
+        out += [rnd.randrange(n_groups)] * rnd.randint(8, 80)
+    return out[:n_chunks]
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_library_and_reference_agree_on_random_maps(seed):
+    rnd = random.Random(1000 + seed)
+    truth = random_groups(rnd, rnd.randint(2, 300))
+    noise, outliers = rnd.choice([5.0, 20.0, 60.0]), rnd.choice([0.0, 0.02, 0.1])
+    got = pl.classify_chunks(len(truth), rates_of(truth, noise=noise, seed=seed, outliers=outliers))
+    want = ref.classify_chunks(len(truth), rates_of(truth, noise=noise, seed=seed, outliers=outliers))
+    assert got == want
+    assert pl.runs_of(got) == ref.runs_of(want)
+    for stack, models, more in ((STACK, 8, 0), (STACK, 8, 3), (1 << 30, 20, 1), (3 << 28, 2, 0), (40 << 30, 1, 0)):
+        assert pl.plan_serving_layout(got, GIB, stack, models, more) == ref.plan_serving_layout(want, GIB, stack, models, more)
+    # the planners also agree on the true map and on maps nobody measured
+    labels = [rnd.randrange(4) for _ in range(rnd.randint(1, 40))] if seed % 2 else truth
+    assert pl.plan_serving_layout(labels, GIB, STACK // 4, 3, 1) == ref.plan_serving_layout(labels, GIB, STACK // 4, 3, 1)
+
+
+def test_classification_options_and_errors():
+    truth = [0] * 40 + [1] * 40 + [2] * 40 + [3] * 40
+    clean = rates_of(truth, noise=1.0, outliers=0.0)
+    assert len(set(pl.classify_chunks(160, clean))) == 4
+    assert len(set(pl.classify_chunks(160, clean, max_groups=2))) == 2
+    assert pl.classify_chunks(160, clean, min_separation=0.2) == [0] * 160          # 4 % apart is not 20 %
+    assert pl.classify_chunks(1, clean) == [0]
+    for max_groups in (2, 3):
+        assert pl.classify_chunks(160, clean, max_groups=max_groups) == ref.classify_chunks(160, clean, max_groups=max_groups)
+    with pytest.raises(ZeroDivisionError):                                           # the caller's exception comes back
+        pl.classify_chunks(8, lambda r, w: 1 / 0)
+    from paper_2505_11204_amd import binding as rb
+    with pytest.raises(rb.RandesError):
+        pl.classify_chunks(0, clean)
+    with pytest.raises(rb.RandesError):
+        pl.plan_serving_layout([0, 1, 2], GIB, 0, 1)
