@@ -31,8 +31,11 @@
  *    graph.  A first call made while its stream is being captured is refused
  *    with RANDES_ENOTSUP before anything is enqueued (call once eagerly
  *    first).  256 argument sets stay cached per process; beyond that the least
- *    recently used one is dropped from the cache (its tables are released by
- *    randes_shutdown(), never in the middle of a call).  Tables of a call made
+ *    recently used one is dropped from the cache.  Its tables are released
+ *    later: once 64 MiB of dropped tables have collected, a first call (which
+ *    allocates and copies synchronously anyway) drains the device and frees
+ *    those that no caller still holds; randes_shutdown() frees the rest.  A
+ *    cached call never frees, synchronises or allocates.  Tables of a call made
  *    while its stream was being captured are kept until randes_shutdown(),
  *    because the graph's kernels point into them (at most 4096 such sets).
  *  - Threads: every entry point may be called from several host threads at

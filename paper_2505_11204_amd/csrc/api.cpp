@@ -152,6 +152,7 @@ struct CachedPlan {
     uint64_t hash = 0;
     int device = 0;
     void *blob = nullptr;     // device tables
+    size_t blob_bytes = 0;
     void *extra = nullptr;    // scratch inside the blob (stats partials)
     bool pinned = false;      // recorded into a HIP graph: its tables must outlive the cache's turnover
     StreamArgs vec{}, scl{};
@@ -168,7 +169,12 @@ using PlanRef = std::shared_ptr<CachedPlan>;
 std::mutex g_mu;
 std::list<PlanRef> g_lru;                                                       // most recently used first
 std::unordered_multimap<uint64_t, std::list<PlanRef>::iterator> g_index;        // by hash of the call
-std::vector<void *> g_retired;    // tables of argument sets dropped from the cache; freed by randes_shutdown()
+// Argument sets dropped from the cache.  Their tables are not freed at once (kernels already enqueued
+// may still read them, and a caller may hold a set it looked up a moment ago): they wait here and
+// are released in batches by reclaim_retired(), the rest by randes_shutdown().
+std::vector<PlanRef> g_retired;
+size_t g_retired_bytes = 0;
+constexpr size_t RETIRED_LIMIT = (size_t)64 << 20;   // retired table bytes that trigger a release
 size_t g_pinned = 0;
 constexpr size_t MAX_PLANS = 256;     // argument sets kept (beyond those recorded into graphs)
 constexpr size_t MAX_PINNED = 4096;   // argument sets recorded into graphs
@@ -192,8 +198,7 @@ void insert_locked(const PlanRef &p)
     g_index.emplace(p->hash, g_lru.begin());
     // Drop the least recently used argument sets beyond the limit, never those a graph refers to.
     // Their tables are not freed here (hipFree waits for the whole device and is not allowed while
-    // a stream is being captured; kernels already enqueued may still read them): they are retired
-    // and released by randes_shutdown().
+    // a stream is being captured; kernels already enqueued may still read them): they are retired.
     size_t loose = g_lru.size() - g_pinned;
     for (auto it = g_lru.end(); loose > MAX_PLANS && it != g_lru.begin();) {
         --it;
@@ -201,9 +206,40 @@ void insert_locked(const PlanRef &p)
         auto range = g_index.equal_range((*it)->hash);
         for (auto ix = range.first; ix != range.second; ++ix)
             if (ix->second == it) { g_index.erase(ix); break; }
-        if ((*it)->blob) g_retired.push_back((*it)->blob);
+        if ((*it)->blob) { g_retired_bytes += (*it)->blob_bytes; g_retired.push_back(*it); }
         it = g_lru.erase(it);
         --loose;
+    }
+}
+
+// Release the retired tables of this device once they add up to RETIRED_LIMIT, so that a loop that
+// cycles over more argument sets than the cache keeps does not grow device memory without bound.
+// Only sets nobody else holds are taken (a holder could still launch with them), and everything
+// launched before is drained first.  Called from the path that has just allocated and copied
+// synchronously itself (a first call, never under capture), never with g_mu held.
+void reclaim_retired(int dev)
+{
+    std::vector<PlanRef> victims;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        if (g_retired_bytes <= RETIRED_LIMIT) return;
+        std::vector<PlanRef> keep;
+        for (PlanRef &p : g_retired) {
+            if (p->device == dev && p.use_count() == 1) { g_retired_bytes -= p->blob_bytes; victims.push_back(std::move(p)); }
+            else keep.push_back(std::move(p));
+        }
+        g_retired.swap(keep);
+    }
+    if (victims.empty()) return;
+    if (hipDeviceSynchronize() != hipSuccess) {   // not now (e.g. a capture elsewhere forbids it): keep them
+        (void)hipGetLastError();
+        std::lock_guard<std::mutex> lock(g_mu);
+        for (PlanRef &p : victims) { g_retired_bytes += p->blob_bytes; g_retired.push_back(std::move(p)); }
+        return;
+    }
+    for (PlanRef &p : victims) {
+        (void)hipFree(p->blob);
+        p->blob = nullptr;
     }
 }
 
@@ -273,15 +309,18 @@ int find_or_build(const CallKey &k, void *hip_stream, PlanRef *out, Build build,
     fresh->hash = h;
     fresh->device = dev;
     if ((rc = build(fresh.get()))) return rc;
-    std::lock_guard<std::mutex> lock(g_mu);
+    std::unique_lock<std::mutex> lock(g_mu);
     PlanRef p = lookup_locked(h, k, dev);
     if (p) {   // another thread built the same tables meanwhile: use those
-        if (fresh->blob) g_retired.push_back(fresh->blob);
+        if (fresh->blob) { g_retired_bytes += fresh->blob_bytes; g_retired.push_back(fresh); }
         *out = p;
         return RANDES_OK;
     }
     insert_locked(fresh);
     *out = fresh;
+    const bool full = g_retired_bytes > RETIRED_LIMIT;
+    lock.unlock();
+    if (full) reclaim_retired(dev);
     return RANDES_OK;
 }
 
@@ -293,6 +332,7 @@ int upload(HostPlan &hp, int n_tasks, CachedPlan *cp)
     pack_tables(hp, &image, &lay);
     hipError_t e = hipMalloc(&cp->blob, lay.total);
     if (e != hipSuccess) { cp->blob = nullptr; return hip_fail(e, "hipMalloc(plan tables)"); }
+    cp->blob_bytes = lay.total;
     e = hipMemcpy(cp->blob, image.data(), image.size(), hipMemcpyHostToDevice);
     if (e != hipSuccess) { (void)hipFree(cp->blob); cp->blob = nullptr; return hip_fail(e, "hipMemcpy(plan tables)"); }
     cp->extra = hp.extra_bytes ? (char *)cp->blob + lay.extra : nullptr;
@@ -978,6 +1018,7 @@ int build_lora_tables(std::vector<LoraItem> &items, const std::vector<LoraSeg> &
     }
     hipError_t e = hipMalloc(&fresh->blob, host.size());
     if (e != hipSuccess) { fresh->blob = nullptr; return hip_fail(e, "hipMalloc(lora tables)"); }
+    fresh->blob_bytes = host.size();
     e = hipMemcpy(fresh->blob, host.data(), host.size(), hipMemcpyHostToDevice);
     if (e != hipSuccess) { (void)hipFree(fresh->blob); fresh->blob = nullptr; return hip_fail(e, "hipMemcpy(lora tables)"); }
     fresh->items_bytes = items_bytes;
@@ -1171,11 +1212,14 @@ int randes_shutdown(void)
             cp->blob = nullptr;
         }
     }
-    for (void *blob : g_retired) {
-        hipError_t e = hipFree(blob);
+    for (const PlanRef &cp : g_retired) {
+        if (!cp->blob) continue;
+        hipError_t e = hipFree(cp->blob);
         if (e != hipSuccess) rc = hip_fail(e, "hipFree(retired plan tables)");
+        cp->blob = nullptr;
     }
     g_retired.clear();
+    g_retired_bytes = 0;
     g_index.clear();
     g_lru.clear();
     g_pinned = 0;

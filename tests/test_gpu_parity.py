@@ -641,6 +641,40 @@ def test_plan_cache_eviction_and_reuse():
         compare(again[l], o_merged[l], "merged again %d" % l)
 
 
+def test_tables_of_dropped_argument_sets_are_released_in_batches():
+    # a loop over far more argument sets than the cache keeps must not grow device memory without bound,
+    # and results stay right across the releases
+    stack = [Layer(8, 256, g % 7, SRSF) for g in range(420)]
+    layers = layers_of(stack)
+    lt = rb.LayerTable(layers)
+    base, deltas = cpu_inputs(stack, 1, "f32")
+    gm, gb = to_gpu(deltas[0]), to_gpu(base)
+    t_m, t_b = rb.PtrTable(gm, lt), rb.PtrTable(gb, lt)
+    out = rb.alloc_like_layers(lt, torch.float32)
+    t_o = rb.PtrTable(out, lt)
+    want = {}
+    for seed in (5, 2500, 7999):
+        o = oracle.retrieve(layers, np_lists(gm), np_lists(gb), seed, 0.5)
+        want[seed] = o
+    torch.cuda.synchronize()
+    free = [torch.cuda.mem_get_info()[0]]
+    for seed in range(8000):
+        rb.retrieve(lt, t_m, t_b, seed, 0.5, out=t_o)
+        if seed in want:
+            torch.cuda.synchronize()
+            for l in (0, 211, 419):
+                bits_equal(out[l], want[seed][l], "seed %d layer %d" % (seed, l))
+        if seed % 500 == 499:
+            torch.cuda.synchronize()
+            free.append(torch.cuda.mem_get_info()[0])
+    used = [(free[0] - f) >> 20 for f in free]
+    print("device memory taken after every 500 argument sets (MiB):", used)
+    # a set's tables are about 30 KB: 8000 sets would hold some 250 MiB if none were released; released in
+    # batches of 64 MiB and more, what is held goes up and down and ends far below that
+    assert max(used) < 160 and used[-1] < 160
+    assert any(b < a for a, b in zip(used, used[1:])), "nothing was ever released"
+
+
 def test_cached_calls_can_be_captured_in_a_graph():
     # once a call's tables are cached it only launches kernels, so it can be recorded into a HIP
     # graph; every replay must give what the eager call gives on the data of that moment
