@@ -569,7 +569,11 @@ int merge_impl(const randes_layer *layers, int32_t n_layers,
             const int rc2 = place(&hp, d, ptrs.data(), n_streams, vector_ok, vec, clamp_rows(kn.merge_rows, burst), eb);
             if (rc2) return rc2;
         }
-        return upload(hp, n_tasks, fresh);
+        const int rc4 = upload(hp, n_tasks, fresh);
+        // up to 8 binary32 tasks: three waves per SIMD by registers, two stream faster on long rows
+        if (!rc4 && !base && n_tasks <= 8 && delta_dtype == RANDES_F32)
+            fresh->vec.lds_floor = wide_row_lds_floor(hp.vec, elem_bytes(delta_dtype));
+        return rc4;
     });
     if (rc) return rc;
     hipStream_t s = (hipStream_t)hip_stream;
@@ -669,7 +673,9 @@ int randes_retrieve(const randes_layer *layers, int32_t n_layers,
             const int rc3 = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(kn.retrieve_rows, burst), eb);
             if (rc3) return rc3;
         }
-        return upload(hp, 1, fresh);
+        const int rc4 = upload(hp, 1, fresh);
+        if (!rc4) fresh->vec.lds_floor = wide_row_lds_floor(hp.vec, elem_bytes(merged_dtype));
+        return rc4;
     });
     if (rc) return rc;
     StreamArgs av = cp->vec, as = cp->scl;
@@ -858,7 +864,9 @@ int randes_update(const randes_layer *layers, int32_t n_layers,
             const int rc3 = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(kn.retrieve_rows, burst), eb);
             if (rc3) return rc3;
         }
-        return upload(hp, 1, fresh);
+        const int rc4 = upload(hp, 1, fresh);
+        if (!rc4) fresh->vec.lds_floor = wide_row_lds_floor(hp.vec, elem_bytes(merged_dtype));
+        return rc4;
     });
     if (rc) return rc;
     StreamArgs av = cp->vec, as = cp->scl;

@@ -11,6 +11,8 @@
 // The shuffle (Sec. 4.3) costs nothing here: it is already folded into the pointer tables.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "device_util.hpp"
 #include "launch.hpp"
 #include "philox.hpp"
@@ -737,7 +739,7 @@ template <int DTI, int DTO, int VEC>
 static hipError_t merge_dispatch(const StreamArgs &a, hipStream_t s)
 {
     const dim3 grid(xcd_grid(a.n_tiles)), block(WG);
-    const size_t lds = sign_bits_lds_bytes(a.n_tasks, VEC);
+    const size_t lds = std::max<size_t>(sign_bits_lds_bytes(a.n_tasks, VEC), a.lds_floor);
     // the element-wise variant and more than KREG_MAX tasks take the any-count kernel
     if constexpr (VEC == 1) {
         hipLaunchKernelGGL((merge_kernel<DTI, DTO, VEC, 0, MERGE_R, false>), grid, block, lds, s, a);
@@ -808,7 +810,7 @@ template <int DTM, int DTB, int VEC>
 static hipError_t retrieve_dispatch(const StreamArgs &a, int dt_out, hipStream_t s)
 {
     const dim3 grid(xcd_grid(a.n_tiles)), block(WG);
-    const size_t lds = sign_bits_lds_bytes(1, VEC);
+    const size_t lds = std::max<size_t>(sign_bits_lds_bytes(1, VEC), a.lds_floor);
     if (dt_out == DT_F32) hipLaunchKernelGGL((retrieve_kernel<DTM, DTB, DT_F32, VEC>), grid, block, lds, s, a);
     else hipLaunchKernelGGL((retrieve_kernel<DTM, DTB, DT_BF16, VEC>), grid, block, lds, s, a);
     return hipGetLastError();
@@ -855,7 +857,8 @@ hipError_t launch_retrieve_many(const StreamArgs &a, int dt, hipStream_t s)
 template <int DTM, int DTD, int VEC>
 static hipError_t update_dispatch(const StreamArgs &a, hipStream_t s)
 {
-    hipLaunchKernelGGL((update_kernel<DTM, DTD, VEC>), dim3(xcd_grid(a.n_tiles)), dim3(WG), sign_bits_lds_bytes(1, VEC), s, a);
+    hipLaunchKernelGGL((update_kernel<DTM, DTD, VEC>), dim3(xcd_grid(a.n_tiles)), dim3(WG),
+                       std::max<size_t>(sign_bits_lds_bytes(1, VEC), a.lds_floor), s, a);
     return hipGetLastError();
 }
 

@@ -143,4 +143,17 @@ void build_coarse_index(SubPlan *sp)
     }
 }
 
+uint32_t wide_row_lds_floor(const SubPlan &sub, size_t elem_bytes)
+{
+    // the length of the row an average byte of the launch lies in; rows as the kernels see them
+    // (folded layers: the longer row)
+    double bytes = 0.0, weighted = 0.0;
+    for (const LayerDev &d : sub.layers) {
+        const double row = (double)d.cols * (double)elem_bytes, b = (double)d.rows * row;
+        bytes += b;
+        weighted += b * row;
+    }
+    return bytes > 0.0 && weighted / bytes >= (double)WIDE_ROW_BYTES ? TWO_WORKGROUP_LDS : 0u;
+}
+
 }  // namespace randes

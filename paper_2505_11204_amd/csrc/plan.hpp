@@ -46,7 +46,20 @@ struct StreamArgs {
     uint32_t key2_lo, key2_hi;    // stats: the second model's seed
     double *partials;             // stats: one triple per workgroup
     uint32_t partial_base;        // stats: index of this launch's first triple
+    uint32_t lds_floor;           // dynamic LDS to request at least (bytes; 0 = what the kernel needs): see wide_row_lds_floor()
 };
+
+// Two workgroups per CU instead of three.  Measured on MI355X: retrieve, hot swap and the merge of up
+// to 8 binary32 tasks stream 1-2 % faster with two workgroups (8 waves) per CU than with the three
+// their registers allow, on stacks of long rows; on stacks of short rows (T5-base: 1.5 to 4 KB)
+// and for the kernels that keep fewer bytes in flight per wave (the any-count merge, the read-only
+// diagnostics) more workgroups are better.  Occupancy is set per launch by the size of the LDS
+// request: 80 KB of the CU's 160 KB leave room for two workgroups.
+constexpr uint32_t WIDE_ROW_BYTES = 6144;       // row length, averaged over the launch's bytes, from which the launch is capped
+constexpr uint32_t TWO_WORKGROUP_LDS = 81920;
+struct SubPlan;
+uint32_t wide_row_lds_floor(const SubPlan &sub, size_t elem_bytes);
+
 
 // A sub-plan: the layers one kernel variant handles (vector or element-wise).
 struct SubPlan {
