@@ -77,21 +77,23 @@ __device__ __forceinline__ uint32_t sign_word(uint32_t bits)
     }
 }
 
+// XOR mask of raw dword j out of the sign word: flips the sign of every element of the dword whose bit is set.
+template <int DT, int VEC>
+__device__ __forceinline__ uint32_t flip_mask(uint32_t W, int j)
+{
+    if constexpr (DT == DT_F32) return (W << (31 - j)) & 0x80000000u;
+    else if constexpr (VEC == 1) return (W & 1u) << 15;
+    else return (W << (3 - j)) & 0x80008000u;
+}
+
 // acc[j] += (+/-) x[j] with the masks rebuilt from the sign word (keeps registers for loads).
 template <int DT, int VEC>
 __device__ __forceinline__ void accumulate_w(const uint32_t (&raw)[NumWords<DT, VEC>::value], uint32_t W, float (&acc)[VEC])
 {
     constexpr int NW = NumWords<DT, VEC>::value;
     uint32_t t[NW];
-    if constexpr (DT == DT_F32) {
 #pragma unroll
-        for (int j = 0; j < NW; ++j) t[j] = raw[j] ^ ((W << (31 - j)) & 0x80000000u);
-    } else if constexpr (VEC == 1) {
-        t[0] = raw[0] ^ ((W & 1u) << 15);
-    } else {
-#pragma unroll
-        for (int j = 0; j < NW; ++j) t[j] = raw[j] ^ ((W << (3 - j)) & 0x80008000u);
-    }
+    for (int j = 0; j < NW; ++j) t[j] = raw[j] ^ flip_mask<DT, VEC>(W, j);
     float v[VEC];
     widen<DT, VEC>(t, v);
 #pragma unroll
@@ -133,7 +135,7 @@ __device__ __forceinline__ void pack_out(const float (&v)[VEC], uint32_t (&w)[Ou
         w[0] = bf16_rne(v[0]);
     } else {
 #pragma unroll
-        for (int j = 0; j < VEC / 2; ++j) w[j] = bf16_rne(v[2 * j]) | (bf16_rne(v[2 * j + 1]) << 16);
+        for (int j = 0; j < VEC / 2; ++j) w[j] = pack_bf16x2(v[2 * j], v[2 * j + 1]);
     }
 }
 
@@ -427,6 +429,13 @@ __device__ __forceinline__ void two_input_bursts(const StreamArgs &A, const Tile
     if (!t.active) return;
     uint32_t bits = lane_bits_from_lds<VEC>(sbits, t, nblk, 0u);
     if (A.negate) bits = ~bits;
+    // The flip acts on X's raw dwords (bf16: one XOR per pair of elements), with the masks made once per lane.
+    uint32_t xm[NWX];
+    {
+        const uint32_t W = sign_word<DTX, VEC>(bits);
+#pragma unroll
+        for (int j = 0; j < NWX; ++j) xm[j] = flip_mask<DTX, VEC>(W, j);
+    }
     const float lambda = A.lambda;
     // The plan gives a wave at most R rows of a tile, so this one burst is all its work.
     uint32_t res[R][NWO];
@@ -434,13 +443,13 @@ __device__ __forceinline__ void two_input_bursts(const StreamArgs &A, const Tile
     for (int u = 0; u < R; ++u)
         if (r + t.WY * u < t.row_end) {
             float x[VEC], y[VEC], o[VEC];
-            widen<DTX, VEC>(rx[u], x);
+            uint32_t fx[NWX];
+#pragma unroll
+            for (int j = 0; j < NWX; ++j) fx[j] = rx[u][j] ^ xm[j];
+            widen<DTX, VEC>(fx, x);
             widen<DTY, VEC>(ry[u], y);
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) {
-                const float xs = u2f(f2u(x[j]) ^ ((bits << (31 - j)) & 0x80000000u));
-                o[j] = FMA ? __builtin_fmaf(lambda, xs, y[j]) : (y[j] + xs);
-            }
+            for (int j = 0; j < VEC; ++j) o[j] = FMA ? __builtin_fmaf(lambda, x[j], y[j]) : (y[j] + x[j]);
             pack_out<DTO, VEC>(o, res[u]);
         }
     load_store_fence();

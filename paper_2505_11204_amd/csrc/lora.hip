@@ -54,19 +54,7 @@
 namespace randes {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-// Two binary32 values -> one dword of two bf16, with the hardware's packed round-to-nearest-even
-// conversion (v_cvt_pk_bf16_f32).  Used only here, where results are checked to a tolerance; the
-// streaming kernels use the integer sequence whose every bit the oracle reproduces.
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
-{
-    f32x2 v;
-    v.x = lo; v.y = hi;
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-}
 
 constexpr int KCH = LORA_DEPTH_SLICE;   // depth values per slice (one 32x32x16 MFMA, or eight 32x32x2)
 constexpr int LORA_SIGN_SEGS = 32;      // segments whose sign bits a workgroup keeps in LDS

@@ -225,6 +225,34 @@ def test_special_values():
                                   wb_.view(np.uint32 if dt == "f32" else np.uint16))
 
 
+@pytest.mark.parametrize("cols", [1024, 1021])
+def test_bf16_rounding_at_every_boundary(cols):
+    # binary32 -> bf16 on the way out of merge and retrieve, for every one of the 65536 high halves (every
+    # exponent, NaNs, infinities and subnormals among them) with low halves at, next to and between the
+    # ties.  1024 columns: 16-byte accesses; 1021: the element-wise kernels.
+    lows = np.array([0x0000, 0x0001, 0x4000, 0x7fff, 0x8000, 0x8001, 0xc000, 0xffff], dtype=np.uint32)
+    u = ((np.arange(65536, dtype=np.uint32)[:, None] << 16) | lows[None, :]).reshape(-1)
+    rows = -(-u.size // cols)
+    u = np.concatenate([u, u[:rows * cols - u.size]])
+    x = torch.from_numpy(u.view(np.float32).reshape(rows, cols).copy())
+    stack = [Layer(rows, cols, -1, FLIP)]
+    layers = layers_of(stack)
+
+    def same(got, want, what):
+        gf, wf = got.float().cpu().numpy(), oracle.bf16_to_f32(want)
+        assert np.array_equal(np.isnan(gf), np.isnan(wf)), what
+        ok = ~np.isnan(wf)
+        assert np.array_equal(to_np(got)[ok].view(np.uint16), np.asarray(want)[ok].view(np.uint16)), what
+
+    m = rb.merge(layers, [to_gpu([x])], [77], merged_dtype=torch.bfloat16)
+    o_m = oracle.merge(layers, [np_lists([x])], [77], CODE["f32"], CODE["bf16"])
+    same(m[0], o_m[0], "merge")
+    base = [torch.full((rows, cols), -0.0)]     # x + (-0) = x for every x, zeros of either sign included
+    out = rb.retrieve(layers, to_gpu([x]), to_gpu(base), 77, 1.0, out_dtype=torch.bfloat16)
+    o_out = oracle.retrieve(layers, np_lists([x]), np_lists(base), 77, 1.0, CODE["f32"], CODE["f32"], CODE["bf16"])
+    same(out[0], o_out[0], "retrieve")
+
+
 def test_empty_and_invalid_requests_are_rejected():
     stack = [Layer(8, 256, 0, SRSF)] * 2
     layers = layers_of(stack)
