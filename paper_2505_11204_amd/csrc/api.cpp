@@ -98,6 +98,19 @@ namespace {
 // A wave handles one burst of at most `burst` rows; the knob can only shrink it.
 int clamp_rows(int knob, int burst) { return (knob <= 0 || knob > burst) ? burst : knob; }
 
+// The same for retrieve and hot swap, whose default depends on the size of the stack.
+int two_input_rows_for(int knob, int burst, double stream_bytes)
+{
+    return knob > 0 ? clamp_rows(knob, burst) : two_input_default_rows(burst, stream_bytes);
+}
+
+double stack_bytes(const randes_layer *layers, int32_t n_layers, int dtype)
+{
+    double b = 0.0;
+    for (int32_t l = 0; l < n_layers; ++l) b += (double)layers[l].rows * (double)layers[l].cols * (double)elem_bytes(dtype);
+    return b;
+}
+
 // ------------------------------------------------------------------ plan cache
 // A call's device tables are found by what the call was given: the kind of call, the layer list,
 // every pointer and seed.  The arguments are hashed where they lie (no copy on the cached path) and
@@ -657,6 +670,7 @@ int randes_retrieve(const randes_layer *layers, int32_t n_layers,
         const int rc2 = build_source_table(layers, n_layers, seed, &src, &why2);
         if (rc2) return fail(rc2, why2);
         const int vec = retrieve_vec(merged_dtype, base_dtype);
+        const double flipped_bytes = stack_bytes(layers, n_layers, merged_dtype);
         for (int32_t l = 0; l < n_layers; ++l) {
             const int32_t t = src[(size_t)l];
             LayerDev d{};
@@ -670,7 +684,7 @@ int randes_retrieve(const randes_layer *layers, int32_t n_layers,
             const bool vector_ok = (layers[l].cols % vec) == 0 && aligned16(d.dst) && aligned16(d.a) && aligned16(d.b);
             const int burst = two_input_burst_rows(merged_dtype, base_dtype, vector_ok ? vec : 1);
             const StreamBytes eb{ elem_bytes(out_dtype), elem_bytes(merged_dtype), elem_bytes(base_dtype), 0 };
-            const int rc3 = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(kn.retrieve_rows, burst), eb);
+            const int rc3 = place(&hp, d, nullptr, 0, vector_ok, vec, two_input_rows_for(kn.retrieve_rows, burst, flipped_bytes), eb);
             if (rc3) return rc3;
         }
         const int rc4 = upload(hp, 1, fresh);
@@ -850,6 +864,7 @@ int randes_update(const randes_layer *layers, int32_t n_layers,
         const int rc2 = build_source_table(layers, n_layers, seed, &src, &why2);
         if (rc2) return fail(rc2, why2);
         const int vec = update_vec(merged_dtype, delta_dtype);
+        const double flipped_bytes = stack_bytes(layers, n_layers, delta_dtype);
         for (int32_t l = 0; l < n_layers; ++l) {
             LayerDev d{};
             d.dst = merged[l];
@@ -861,7 +876,7 @@ int randes_update(const randes_layer *layers, int32_t n_layers,
             const bool vector_ok = (layers[l].cols % vec) == 0 && aligned16(d.dst) && aligned16(d.a);
             const int burst = two_input_burst_rows(delta_dtype, merged_dtype, vector_ok ? vec : 1);
             const StreamBytes eb{ elem_bytes(merged_dtype), elem_bytes(delta_dtype), 0, 0 };
-            const int rc3 = place(&hp, d, nullptr, 0, vector_ok, vec, clamp_rows(kn.retrieve_rows, burst), eb);
+            const int rc3 = place(&hp, d, nullptr, 0, vector_ok, vec, two_input_rows_for(kn.retrieve_rows, burst, flipped_bytes), eb);
             if (rc3) return rc3;
         }
         const int rc4 = upload(hp, 1, fresh);

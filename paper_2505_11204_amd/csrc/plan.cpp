@@ -143,6 +143,14 @@ void build_coarse_index(SubPlan *sp)
     }
 }
 
+int two_input_default_rows(int burst, double stream_bytes)
+{
+    double share = stream_bytes / 3.2e9;
+    share = share < 0.375 ? 0.375 : (share > 0.75 ? 0.75 : share);
+    const int rows = (int)(burst * share + 0.5);
+    return rows < 1 ? 1 : rows;
+}
+
 uint32_t wide_row_lds_floor(const SubPlan &sub, size_t elem_bytes)
 {
     // the length of the row an average byte of the launch lies in; rows as the kernels see them

@@ -60,6 +60,16 @@ constexpr uint32_t TWO_WORKGROUP_LDS = 81920;
 struct SubPlan;
 uint32_t wide_row_lds_floor(const SubPlan &sub, size_t elem_bytes);
 
+// Rows a wave of retrieve or hot swap takes of its tile when the caller has not set the knob: a share
+// of the kernel's burst of `burst` rows that grows with the bytes of the stream the flip acts on.
+// A workgroup lives about as long as the memory takes to serve what all resident workgroups have
+// asked for (15 us with full bursts), and at the end of a launch the last ones finish one by one
+// over that time, so a stack the chip streams in a few hundred microseconds wants short-lived
+// workgroups: 3/8 of the burst up to 1.2 GB.  Long launches take 3/4 of it (from 2.4 GB): measured
+// on MI355X, two workgroups per CU with 12 rows a wave, or three with 8, stream 0.4 % faster than
+// two with 16, and fewer rows in flight than that lose again.
+int two_input_default_rows(int burst, double stream_bytes);
+
 
 // A sub-plan: the layers one kernel variant handles (vector or element-wise).
 struct SubPlan {
