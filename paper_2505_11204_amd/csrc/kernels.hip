@@ -100,6 +100,21 @@ __device__ __forceinline__ void accumulate_w(const uint32_t (&raw)[NumWords<DT, 
     for (int j = 0; j < VEC; ++j) acc[j] = acc[j] + v[j];
 }
 
+// The same with the XOR masks of the raw dwords handed in ready-made.
+template <int DT, int VEC>
+__device__ __forceinline__ void accumulate_m(const uint32_t (&raw)[NumWords<DT, VEC>::value],
+                                             const uint32_t (&mask)[NumWords<DT, VEC>::value], float (&acc)[VEC])
+{
+    constexpr int NW = NumWords<DT, VEC>::value;
+    uint32_t t[NW];
+#pragma unroll
+    for (int j = 0; j < NW; ++j) t[j] = raw[j] ^ mask[j];
+    float v[VEC];
+    widen<DT, VEC>(t, v);
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) acc[j] = acc[j] + v[j];
+}
+
 // acc[j] += (+/-) (theta[j] - base[j]): the delta Delta_i = Theta_i - Theta_0 (Sec. 3) formed in
 // binary32 on the fly, one rounding, then flipped and added like a stored delta.
 template <int DT, int VEC>
@@ -311,6 +326,20 @@ __global__ void __launch_bounds__(WG) merge_kernel(const StreamArgs A)
             const uint32_t bits = lane_bits_from_lds<VEC>(sbits, t, nblk, i);
             W[i] = SUB ? bits : sign_word<DTI, VEC>(bits);
         }
+        // bf16 pairs: every task's XOR masks made once and kept in registers for all R rows (the asm
+        // keeps the compiler from rebuilding them row by row, which it otherwise prefers); a raw dword
+        // then costs one XOR, and the widening of its two halves folds into it.
+        constexpr bool MASKS = !SUB && DTI == DT_BF16 && VEC > 1;
+        uint32_t M[MASKS ? KT : 1][NW];
+        if constexpr (MASKS) {
+#pragma unroll
+            for (int i = 0; i < KT; ++i)
+#pragma unroll
+                for (int q = 0; q < NW; ++q) {
+                    M[i][q] = flip_mask<DTI, VEC>(W[i], q);
+                    asm volatile("" : "+v"(M[i][q]));
+                }
+        }
         // The plan gives a wave at most R rows of a tile, so this one burst is all its work.
         uint32_t res[R][NWO];
 #pragma unroll
@@ -322,6 +351,7 @@ __global__ void __launch_bounds__(WG) merge_kernel(const StreamArgs A)
 #pragma unroll
                 for (int i = 0; i < KT; ++i) {
                     if constexpr (SUB) accumulate_sub<DTI, VEC>(raw[j][i], raw[j][KT + i], W[i], acc);
+                    else if constexpr (MASKS) accumulate_m<DTI, VEC>(raw[j][i], M[i], acc);
                     else accumulate_w<DTI, VEC>(raw[j][i], W[i], acc);
                 }
                 pack_out<DTO, VEC>(acc, res[j]);
@@ -373,8 +403,14 @@ __global__ void __launch_bounds__(WG) merge_kernel(const StreamArgs A)
                                     if (ok1) accumulate_sub<DTI, VEC>(raw[1][q], raw[1][KC + q], bits, acc[1]);
                                 } else {
                                     const uint32_t W = sign_word<DTI, VEC>(bits);
-                                    accumulate_w<DTI, VEC>(raw[0][q], W, acc[0]);
-                                    if (ok1) accumulate_w<DTI, VEC>(raw[1][q], W, acc[1]);
+                                    uint32_t Mq[NW];   // one set of masks for both rows (see M above)
+#pragma unroll
+                                    for (int w = 0; w < NW; ++w) {
+                                        Mq[w] = flip_mask<DTI, VEC>(W, w);
+                                        if constexpr (DTI == DT_BF16 && VEC > 1) asm volatile("" : "+v"(Mq[w]));
+                                    }
+                                    accumulate_m<DTI, VEC>(raw[0][q], Mq, acc[0]);
+                                    if (ok1) accumulate_m<DTI, VEC>(raw[1][q], Mq, acc[1]);
                                 }
                             }
                         }
