@@ -99,9 +99,10 @@ namespace {
 int clamp_rows(int knob, int burst) { return (knob <= 0 || knob > burst) ? burst : knob; }
 
 // The same for retrieve and hot swap, whose default depends on the size of the stack.
-int two_input_rows_for(int knob, int burst, double stream_bytes)
+// (Element-wise layers keep the full burst: their lanes hold 2 or 4 bytes a row, not 16.)
+int two_input_rows_for(int knob, int burst, double stream_bytes, bool vector_ok)
 {
-    return knob > 0 ? clamp_rows(knob, burst) : two_input_default_rows(burst, stream_bytes);
+    return (knob > 0 || !vector_ok) ? clamp_rows(knob, burst) : two_input_default_rows(burst, stream_bytes);
 }
 
 double stack_bytes(const randes_layer *layers, int32_t n_layers, int dtype)
@@ -684,7 +685,7 @@ int randes_retrieve(const randes_layer *layers, int32_t n_layers,
             const bool vector_ok = (layers[l].cols % vec) == 0 && aligned16(d.dst) && aligned16(d.a) && aligned16(d.b);
             const int burst = two_input_burst_rows(merged_dtype, base_dtype, vector_ok ? vec : 1);
             const StreamBytes eb{ elem_bytes(out_dtype), elem_bytes(merged_dtype), elem_bytes(base_dtype), 0 };
-            const int rc3 = place(&hp, d, nullptr, 0, vector_ok, vec, two_input_rows_for(kn.retrieve_rows, burst, flipped_bytes), eb);
+            const int rc3 = place(&hp, d, nullptr, 0, vector_ok, vec, two_input_rows_for(kn.retrieve_rows, burst, flipped_bytes, vector_ok), eb);
             if (rc3) return rc3;
         }
         const int rc4 = upload(hp, 1, fresh);
@@ -876,7 +877,7 @@ int randes_update(const randes_layer *layers, int32_t n_layers,
             const bool vector_ok = (layers[l].cols % vec) == 0 && aligned16(d.dst) && aligned16(d.a);
             const int burst = two_input_burst_rows(delta_dtype, merged_dtype, vector_ok ? vec : 1);
             const StreamBytes eb{ elem_bytes(merged_dtype), elem_bytes(delta_dtype), 0, 0 };
-            const int rc3 = place(&hp, d, nullptr, 0, vector_ok, vec, two_input_rows_for(kn.retrieve_rows, burst, flipped_bytes), eb);
+            const int rc3 = place(&hp, d, nullptr, 0, vector_ok, vec, two_input_rows_for(kn.retrieve_rows, burst, flipped_bytes, vector_ok), eb);
             if (rc3) return rc3;
         }
         const int rc4 = upload(hp, 1, fresh);

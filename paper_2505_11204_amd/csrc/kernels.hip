@@ -625,19 +625,29 @@ __global__ void __launch_bounds__(WG) stats_kernel(const StreamArgs A)
     double s_ab = 0.0, s_aa = 0.0, s_bb = 0.0;
     if (t.active) {
         const uint32_t bits = lane_bits_from_lds<VEC>(sbits, t, nblk, 0u) ^ lane_bits_from_lds<VEC>(sbits + nblk * 4u, t, nblk, 0u);
+        uint32_t am[NW];   // both flips on a, as XOR masks of its raw dwords
+        {
+            const uint32_t W = sign_word<DT, VEC>(bits);
+#pragma unroll
+            for (int j = 0; j < NW; ++j) am[j] = flip_mask<DT, VEC>(W, j);
+        }
 #pragma unroll
         for (int u = 0; u < R; ++u)
             if (r + t.WY * u < t.row_end) {
                 float x[VEC], y[VEC];
-                widen<DT, VEC>(ra[u], x);
+                uint32_t fa[NW];
+#pragma unroll
+                for (int j = 0; j < NW; ++j) fa[j] = ra[u][j] ^ am[j];
+                widen<DT, VEC>(fa, x);
                 widen<DT, VEC>(rb[u], y);
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) {
-                    const double xa = (double)u2f(f2u(x[j]) ^ ((bits << (31 - j)) & 0x80000000u));   // both flips on a
-                    const double yb = (double)y[j];
-                    s_ab += xa * yb;
-                    s_aa += xa * xa;
-                    s_bb += yb * yb;
+                    // A product of two binary32 values is exact in binary64, so the fused form rounds
+                    // exactly as a multiplication followed by an addition would: one instruction, same bits.
+                    const double xa = (double)x[j], yb = (double)y[j];
+                    s_ab = __builtin_fma(xa, yb, s_ab);
+                    s_aa = __builtin_fma(xa, xa, s_aa);
+                    s_bb = __builtin_fma(yb, yb, s_bb);
                 }
             }
     }
