@@ -67,7 +67,8 @@ uint32_t wide_row_lds_floor(const SubPlan &sub, size_t elem_bytes);
 // over that time, so a stack the chip streams in a few hundred microseconds wants short-lived
 // workgroups: 3/8 of the burst up to 1.2 GB.  Long launches take 3/4 of it (from 2.4 GB): measured
 // on MI355X, two workgroups per CU with 12 rows a wave, or three with 8, stream 0.4 % faster than
-// two with 16, and fewer rows in flight than that lose again.
+// two with 16, and fewer rows in flight than that lose again.  Hot swap works in place and takes
+// the short burst at every size (it passes 0 bytes).
 int two_input_default_rows(int burst, double stream_bytes);
 
 
