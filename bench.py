@@ -60,6 +60,8 @@ PAPER_RETRIEVE_MS = {
 PROFILES = {
     "llama_7b": "profiles/llama_7b_bf16_k8_merge_retrieve.txt",
     "vit_l14": "profiles/vit_l14_f32_k20_merge_retrieve.txt",
+    "vit_b32": "profiles/vit_b32_f32_k8_merge_retrieve.txt",
+    "t5_base": "profiles/t5_base_bf16_k8_merge_retrieve.txt",
 }
 KERNEL_SOURCES = ("paper_2505_11204_amd/csrc/kernels.hip", "paper_2505_11204_amd/csrc/device_util.hpp",
                   "paper_2505_11204_amd/csrc/philox.hpp")
