@@ -16,9 +16,10 @@
 extern "C" {
 #endif
 
-/* Launch-shape knob: rows of a tile that one wavefront owns
- * (0 = built-in default, the kernels' burst size; larger values are clamped to
- * it).  Results never depend on them.  Returns RANDES_EINVAL for negative values. */
+/* Launch-shape knob: rows of a tile that one wavefront owns (0 = built-in default: the kernels'
+ * burst size for merge and the diagnostics, a share of it chosen by the size of the stack for
+ * retrieve and hot swap; values above the burst size are clamped to it).  Results never depend on
+ * them.  Returns RANDES_EINVAL for negative values. */
 int randes_set_tile_rows(int32_t merge_rows, int32_t retrieve_rows);
 
 /* Second launch-shape knob: how many of a workgroup's 4 wavefronts may sit side by
