@@ -57,6 +57,7 @@ struct StreamArgs {
 // request: 80 KB of the CU's 160 KB leave room for two workgroups.
 constexpr uint32_t WIDE_ROW_BYTES = 6144;       // row length, averaged over the launch's bytes, from which the launch is capped
 constexpr uint32_t TWO_WORKGROUP_LDS = 81920;
+constexpr uint64_t LONG_ROW_BYTES = 20480;      // row length from which a layer's tiles are as wide as they can be without idling more lanes
 struct SubPlan;
 uint32_t wide_row_lds_floor(const SubPlan &sub, size_t elem_bytes);
 
