@@ -64,7 +64,8 @@ PROFILES = {
     "t5_base": "profiles/t5_base_bf16_k8_merge_retrieve.txt",
 }
 KERNEL_SOURCES = ("paper_2505_11204_amd/csrc/kernels.hip", "paper_2505_11204_amd/csrc/device_util.hpp",
-                  "paper_2505_11204_amd/csrc/philox.hpp")
+                  "paper_2505_11204_amd/csrc/philox.hpp", "paper_2505_11204_amd/csrc/plan.cpp",
+                  "paper_2505_11204_amd/csrc/plan.hpp")
 
 
 def parse():
