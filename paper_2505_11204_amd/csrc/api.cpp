@@ -587,6 +587,8 @@ int merge_impl(const randes_layer *layers, int32_t n_layers,
         // up to 8 binary32 tasks: three waves per SIMD by registers, two stream faster on long rows
         if (!rc4 && !base && n_tasks <= 8 && delta_dtype == RANDES_F32)
             fresh->vec.lds_floor = wide_row_lds_floor(hp.vec, elem_bytes(delta_dtype));
+        if (!rc4 && !base && (double)n_tasks * stack_bytes(layers, n_layers, delta_dtype) < MERGE_CHUNKED_BELOW_BYTES)
+            fresh->vec.xcd_chunk_shift = MERGE_CHUNK_SHIFT;
         return rc4;
     });
     if (rc) return rc;

@@ -197,8 +197,12 @@ struct Tile {
 
 constexpr uint32_t N_XCD = 8;   // workgroup i of a launch is dispatched to XCD i mod 8
 
-// Launch size for n_tiles tiles: a multiple of the XCD count (see locate()).
-static inline uint32_t xcd_grid(uint32_t n_tiles) { return (n_tiles + N_XCD - 1u) / N_XCD * N_XCD; }
+// Launch size for n_tiles tiles: a multiple of the XCD count, or of a round of chunks (see locate()).
+static inline uint32_t xcd_grid(uint32_t n_tiles, uint32_t chunk_shift = 0)
+{
+    const uint32_t q = N_XCD << chunk_shift;
+    return (n_tiles + q - 1u) / q * q;
+}
 
 template <int VEC>
 __device__ __forceinline__ Tile locate(const StreamArgs &A)
@@ -206,8 +210,11 @@ __device__ __forceinline__ Tile locate(const StreamArgs &A)
     // Workgroups are handed to the 8 XCDs round-robin.  Give XCD x the x-th contiguous eighth of the
     // tile sequence, so that each XCD (own L2, own address-translation cache) sweeps one region of
     // every stream front to back instead of touching all of them: measured +5..8 % bandwidth.
-    const uint32_t per_xcd = gridDim.x / N_XCD;
-    const uint32_t bid = (blockIdx.x % N_XCD) * per_xcd + blockIdx.x / N_XCD;
+    // With chunks (A.xcd_chunk_shift = s > 0) the XCDs take runs of 1 << s tiles in turn instead: all of
+    // them then work in the same stretch of the stack and finish together, whatever the tiles cost.
+    const uint32_t xi = blockIdx.x / N_XCD, xcd = blockIdx.x % N_XCD, cs = A.xcd_chunk_shift;
+    const uint32_t bid = cs ? ((((xi >> cs) * N_XCD + xcd) << cs) + (xi & ((1u << cs) - 1u)))
+                            : xcd * (gridDim.x / N_XCD) + xi;
     Tile t;
     t.valid = bid < A.n_tiles;
     t.id = bid;
@@ -793,7 +800,7 @@ int update_vec(int dt_merged, int dt_delta) { return (dt_merged == DT_BF16 || dt
 template <int DTI, int DTO, int VEC>
 static hipError_t merge_dispatch(const StreamArgs &a, hipStream_t s)
 {
-    const dim3 grid(xcd_grid(a.n_tiles)), block(WG);
+    const dim3 grid(xcd_grid(a.n_tiles, a.xcd_chunk_shift)), block(WG);
     const size_t lds = std::max<size_t>(sign_bits_lds_bytes(a.n_tasks, VEC), a.lds_floor);
     // the element-wise variant and more than KREG_MAX tasks take the any-count kernel
     if constexpr (VEC == 1) {
@@ -815,7 +822,7 @@ static hipError_t merge_dispatch(const StreamArgs &a, hipStream_t s)
 template <int DTI, int DTO, int VEC>
 static hipError_t merge_weights_dispatch(const StreamArgs &a, hipStream_t s)
 {
-    const dim3 grid(xcd_grid(a.n_tiles)), block(WG);
+    const dim3 grid(xcd_grid(a.n_tiles, a.xcd_chunk_shift)), block(WG);
     const size_t lds = sign_bits_lds_bytes(a.n_tasks, VEC);
     constexpr int R = MERGE_WEIGHTS_R;
     if constexpr (VEC == 1) {
@@ -864,7 +871,7 @@ hipError_t launch_merge_weights(const StreamArgs &a, int vec, int dt_in, int dt_
 template <int DTM, int DTB, int VEC>
 static hipError_t retrieve_dispatch(const StreamArgs &a, int dt_out, hipStream_t s)
 {
-    const dim3 grid(xcd_grid(a.n_tiles)), block(WG);
+    const dim3 grid(xcd_grid(a.n_tiles, a.xcd_chunk_shift)), block(WG);
     const size_t lds = std::max<size_t>(sign_bits_lds_bytes(1, VEC), a.lds_floor);
     if (dt_out == DT_F32) hipLaunchKernelGGL((retrieve_kernel<DTM, DTB, DT_F32, VEC>), grid, block, lds, s, a);
     else hipLaunchKernelGGL((retrieve_kernel<DTM, DTB, DT_BF16, VEC>), grid, block, lds, s, a);
@@ -890,7 +897,7 @@ hipError_t launch_retrieve(const StreamArgs &a, int vec, int dt_merged, int dt_b
 template <int DT, int VEC>
 static hipError_t retrieve_many_dispatch(const StreamArgs &a, hipStream_t s)
 {
-    const dim3 grid(xcd_grid(a.n_tiles)), block(WG);
+    const dim3 grid(xcd_grid(a.n_tiles, a.xcd_chunk_shift)), block(WG);
     const size_t lds = sign_bits_lds_bytes(a.n_tasks, VEC);
     switch (a.n_tasks) {
     case 2: hipLaunchKernelGGL((retrieve_many_kernel<DT, VEC, 2>), grid, block, lds, s, a); break;
@@ -912,7 +919,7 @@ hipError_t launch_retrieve_many(const StreamArgs &a, int dt, hipStream_t s)
 template <int DTM, int DTD, int VEC>
 static hipError_t update_dispatch(const StreamArgs &a, hipStream_t s)
 {
-    hipLaunchKernelGGL((update_kernel<DTM, DTD, VEC>), dim3(xcd_grid(a.n_tiles)), dim3(WG),
+    hipLaunchKernelGGL((update_kernel<DTM, DTD, VEC>), dim3(xcd_grid(a.n_tiles, a.xcd_chunk_shift)), dim3(WG),
                        std::max<size_t>(sign_bits_lds_bytes(1, VEC), a.lds_floor), s, a);
     return hipGetLastError();
 }
@@ -938,7 +945,7 @@ int stats_vec(int dt) { return dt == DT_BF16 ? 8 : 4; }
 hipError_t launch_stats(const StreamArgs &a, int vec, int dt, hipStream_t s)
 {
     if (a.n_tiles == 0) return hipSuccess;
-    const dim3 grid(xcd_grid(a.n_tiles)), block(WG);
+    const dim3 grid(xcd_grid(a.n_tiles, a.xcd_chunk_shift)), block(WG);
     const size_t lds = 2 * sign_bits_lds_bytes(1, vec ? stats_vec(dt) : 1);
     if (vec) {
         if (dt == DT_F32) hipLaunchKernelGGL((stats_kernel<DT_F32, 4>), grid, block, lds, s, a);

@@ -47,6 +47,8 @@ struct StreamArgs {
     double *partials;             // stats: one triple per workgroup
     uint32_t partial_base;        // stats: index of this launch's first triple
     uint32_t lds_floor;           // dynamic LDS to request at least (bytes; 0 = what the kernel needs): see wide_row_lds_floor()
+    uint32_t xcd_chunk_shift;     // how the tile sequence is dealt to the 8 XCDs: 0 = one contiguous eighth each,
+                                  // s > 0 = chunks of 1 << s tiles in turn (see locate() in kernels.hip)
 };
 
 // Two workgroups per CU instead of three.  Measured on MI355X: retrieve, hot swap and the merge of up
@@ -57,6 +59,12 @@ struct StreamArgs {
 // request: 80 KB of the CU's 160 KB leave room for two workgroups.
 constexpr uint32_t WIDE_ROW_BYTES = 6144;       // row length, averaged over the launch's bytes, from which the launch is capped
 constexpr uint32_t TWO_WORKGROUP_LDS = 81920;
+// The merge of deltas deals its tiles to the XCDs in chunks of 32 instead of one contiguous eighth each
+// when it reads less than 80 GB: measured on MI355X, T5-base +4.7 %, ViT-B/32 +3.6 %, ViT-L/14 +1.2 %,
+// 8 to 24 Llama blocks +1 % (with ordinary allocations 3.6 to 5 % on the three small stacks); from 29 blocks
+// (94 GB) on the contiguous order is 0.4-0.5 % faster.  Retrieve is slower with chunks at every size.
+constexpr uint32_t MERGE_CHUNK_SHIFT = 5;
+constexpr double MERGE_CHUNKED_BELOW_BYTES = 80e9;
 constexpr uint64_t LONG_ROW_BYTES = 20480;      // row length from which a layer's tiles are as wide as they can be without idling more lanes
 struct SubPlan;
 uint32_t wide_row_lds_floor(const SubPlan &sub, size_t elem_bytes);
