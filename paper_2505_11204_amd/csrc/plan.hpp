@@ -51,9 +51,10 @@ struct StreamArgs {
                                   // s > 0 = chunks of 1 << s tiles in turn (see locate() in kernels.hip)
 };
 
-// Two workgroups per CU instead of three.  Measured on MI355X: retrieve, hot swap and the merge of up
-// to 8 binary32 tasks stream 1-2 % faster with two workgroups (8 waves) per CU than with the three
-// their registers allow, on stacks of long rows; on stacks of short rows (T5-base: 1.5 to 4 KB)
+// Two workgroups per CU instead of three.  Measured on MI355X: retrieve, hot swap and the merge of 3
+// to 8 tasks held in registers stream 1-3 % faster with two workgroups (8 waves) per CU than with the
+// three or four their registers allow, on stacks of long rows (with 2 tasks too little is in flight
+// then: -8 %); on stacks of short rows (T5-base: 1.5 to 4 KB)
 // and for the kernels that keep fewer bytes in flight per wave (the any-count merge, the read-only
 // diagnostics) more workgroups are better.  Occupancy is set per launch by the size of the LDS
 // request: 80 KB of the CU's 160 KB leave room for two workgroups.
