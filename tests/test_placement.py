@@ -155,3 +155,26 @@ def test_classification_options_and_errors():
         pl.classify_chunks(0, clean)
     with pytest.raises(rb.RandesError):
         pl.plan_serving_layout([0, 1, 2], GIB, 0, 1)
+
+
+def test_benchmark_places_a_write_only_buffer_across_a_group_boundary():
+    import os
+    import sys
+    from types import SimpleNamespace
+    sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    import bench
+    chunk = 1 << 30
+    labels = [1] * 96 + [0] * 96 + [2] * 82
+    fake = SimpleNamespace(arena=SimpleNamespace(chunk_bytes=chunk), labels=labels)
+    nbytes = 679_477_248
+    off = bench.across_a_boundary(fake, nbytes)
+    assert off % 256 == 0
+    assert off < 96 * chunk < off + nbytes                        # the first boundary lies inside the buffer
+    assert abs((96 * chunk - off) - nbytes // 2) < 256            # half of it on either side
+    # a boundary whose neighbouring runs are too short for half the buffer is passed over
+    labels = [1] * 4 + [0] * 1 + [2] * 8 + [1] * 8
+    fake = SimpleNamespace(arena=SimpleNamespace(chunk_bytes=chunk), labels=labels)
+    off = bench.across_a_boundary(fake, 6 * chunk)
+    assert off == 13 * chunk - 3 * chunk
+    assert bench.across_a_boundary(SimpleNamespace(arena=SimpleNamespace(chunk_bytes=chunk), labels=[0] * 20), nbytes) is None
+    assert bench.across_a_boundary(None, nbytes) is None
