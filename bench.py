@@ -734,7 +734,7 @@ def main():
             try:
                 gs = W.step_in_a_graph()
             except Exception as e:      # the timed figures above do not depend on this extra
-                gs = {"error": str(e).splitlines()[0][:200], "GBs": float("nan"), "frac_of_hbm_peak": float("nan")}
+                gs = {"error": (str(e).splitlines() or [type(e).__name__])[0][:200]}
                 torch.cuda.synchronize()
             entry["step_replayed_from_a_hip_graph"] = gs
             tw, stale_w = profile_traffic(name)
@@ -743,8 +743,8 @@ def main():
             if name in PAPER_RETRIEVE_MS:
                 entry["paper_retrieve_one_model (context: another machine, not a target)"] = PAPER_RETRIEVE_MS[name]
             others[name] = entry
-            lines.append(one_line(name, mw) + ", step replayed from a HIP graph %.0f GB/s (%.3f)" % (
-                gs["GBs"], gs["frac_of_hbm_peak"]))
+            lines.append(one_line(name, mw) + (", step replayed from a HIP graph %.0f GB/s (%.3f)" % (
+                gs["GBs"], gs["frac_of_hbm_peak"]) if "GBs" in gs else ", step replayed from a HIP graph: failed"))
             del W
             torch.cuda.empty_cache()
         lv = lora_variant(pl)
